@@ -1,0 +1,176 @@
+/*
+ * mmoe -- forward pass of one multi-model MoE layer on AMD MI355X (gfx950).
+ *
+ * Several fine-tuned variants of one MoE model are served from a single
+ * consolidated pool of experts (paper, section 3.1: similar experts of the
+ * variants are loaded once and shared; Algorithm 1 emits the expert map).  At
+ * inference (Algorithm 2, the per-layer body; Figure 3) the requested variant's
+ * own gate scores the token, the top experts are selected, each selected
+ * (variant, expert) is looked up in the map, the resident expert for that
+ * location is applied -- possibly another variant's when the location is
+ * consolidated, the variant's own otherwise -- and the results are combined
+ * with the gate's coefficients (section 3.2).
+ *
+ * This library evaluates that layer for a batch that mixes tokens of several
+ * variants.  Every token carries its variant id; the map is the table
+ * M[v][e] -> pool slot; the pool holds each resident expert once.
+ *
+ * Conventions
+ *   T tokens, d = d_model, f = d_ff, V variants, E experts per variant,
+ *   k = top_k, S pool slots, P = T*k (token, pick) pairs, pair id p = t*k + j.
+ *   All tensors are dense and row-major.  "dtype" is the storage type of X, Wr,
+ *   the pool, H and Y; every product is accumulated in fp32.
+ *
+ * Pointers
+ *   Every pointer except mmoe_shape* is a DEVICE pointer owned by the caller.
+ *   The library never allocates, frees or keeps device memory; scratch comes
+ *   from the caller's workspace `ws` (at least mmoe_workspace_bytes(), 256-byte
+ *   aligned).  Inputs are read-only, outputs are fully overwritten.  `stream`
+ *   is a hipStream_t passed as void*; every call is asynchronous on it and
+ *   never synchronises the host (mmoe_validate_inputs excepted).
+ *
+ * Errors
+ *   0 on success, a negative mmoe_status otherwise.  Only host-checkable faults
+ *   are detected: null pointers, bad dimensions, unsupported combinations,
+ *   small workspace, misalignment, launch failures.  Device data is not
+ *   validated on the hot path: vid[t] outside [0,V), M[v][e] outside [0,S) or
+ *   non-finite logits give undefined results (use mmoe_validate_inputs).
+ *
+ * Limits
+ *   d_model and d_ff multiples of 256; E <= 256; top_k <= min(E, 8); S <= 1024;
+ *   P*max(d,f) < 2^31 * 16.  SWIGLU needs W3, RELU needs W3 == NULL.
+ */
+#ifndef MMOE_H
+#define MMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MMOE_F32 = 0, MMOE_BF16 = 1 } mmoe_dtype;
+typedef enum { MMOE_RELU = 0, MMOE_SWIGLU = 1 } mmoe_act;
+
+typedef enum {
+    MMOE_OK = 0,
+    MMOE_ERR_NULL = -1,      /* a required pointer is NULL                               */
+    MMOE_ERR_DIM = -2,       /* a dimension is not positive                              */
+    MMOE_ERR_TOPK = -3,      /* top_k > E or top_k > 8                                   */
+    MMOE_ERR_DTYPE = -4,     /* unknown dtype or activation code                         */
+    MMOE_ERR_W3 = -5,        /* W3 missing for SWIGLU, or given for RELU                 */
+    MMOE_ERR_WORKSPACE = -6, /* ws is NULL or ws_bytes too small                         */
+    MMOE_ERR_ALIGN = -7,     /* a tensor pointer is not 16-byte (ws: 256-byte) aligned   */
+    MMOE_ERR_MULTIPLE = -8,  /* d_model or d_ff is not a multiple of 256                 */
+    MMOE_ERR_LIMIT = -9,     /* E, S or the problem size exceeds the limits above        */
+    MMOE_ERR_LAUNCH = -10    /* the HIP runtime refused a kernel launch                  */
+} mmoe_status;
+
+typedef struct {
+    int32_t T;       /* tokens in the batch                      */
+    int32_t d_model; /* hidden size d                            */
+    int32_t d_ff;    /* expert inner size f                      */
+    int32_t V;       /* model variants                           */
+    int32_t E;       /* experts per variant                      */
+    int32_t S;       /* slots in the consolidated pool           */
+    int32_t top_k;   /* experts selected per token               */
+    int32_t dtype;   /* mmoe_dtype                               */
+    int32_t act;     /* mmoe_act                                 */
+} mmoe_shape;
+
+/* Host only, pure.  Workspace (bytes) sufficient for every call below, 0 if the shape is invalid. */
+size_t mmoe_workspace_bytes(const mmoe_shape *shape);
+
+/* Host only.  Text for a status code (static storage). */
+const char *mmoe_strerror(int status);
+
+/*
+ * One-time repacking of the pool, done when the pool is loaded (the paper's
+ * loader runs once, offline, before serving: section 3.1).  The boundary's
+ * plain layout is "in x out": W1, W3 [S, d, f] and W2 [S, f, d].  The expert
+ * kernels read the transposed, reduction-dimension-contiguous layout
+ * W1p, W3p [S, f, d] and W2p [S, d, f] that this call writes.  W3/W3p are NULL
+ * for RELU.  Outputs must not overlap inputs.
+ */
+int mmoe_pack_weights(const mmoe_shape *shape, const void *W1, const void *W3, const void *W2,
+                      void *W1p, void *W3p, void *W2p, void *stream);
+
+/*
+ * Step R -- gate of the requested variant (Algorithm 2, "gate(act)"; section 3.2).
+ *   logit[t,e] = <X[t,:], Wr[vid[t],e,:]> (+ br[vid[t],e])
+ *   the k largest logits are selected, ties to the lower expert index, listed in
+ *   selection (descending) order; w[t,j] = softmax over the k selected logits.
+ * The logit is an fp32 sum in a fixed order, so that the selected indices are
+ * reproducible bit for bit: element i belongs to lane (i div 4) mod 64; a lane
+ * accumulates its elements in ascending i with one fused multiply-add each,
+ * starting from +0; the 64 partial sums are combined by the butterfly
+ * "for off in 32,16,8,4,2,1: p[l] = p[l] + p[l xor off]"; the bias is added last.
+ *   X [T,d] dtype; vid [T] int32; Wr [V,E,d] dtype; br [V,E] fp32 or NULL;
+ *   topk_idx [T,k] int32 out; topk_w [T,k] fp32 out.
+ */
+int mmoe_route(const mmoe_shape *shape, const void *X, const int32_t *vid, const void *Wr,
+               const float *br, int32_t *topk_idx, float *topk_w, void *stream);
+
+/*
+ * Steps M and G -- expert-map lookup and grouping by pool slot (Algorithm 2, the
+ * "map[iL][iE]" lookup; section 3.2: a hit uses the resident expert whoever owns it,
+ * a miss the requested variant's own, which here is a private slot).
+ *   slot[p] = M[vid[t]][topk_idx[p]];  counts[s] = #{p : slot[p] = s};
+ *   offsets = exclusive prefix sum of counts, offsets[S] = P;
+ *   perm = pair ids sorted by (slot, p) (stable);  inv_perm[perm[r]] = r;
+ *   Xg[r,:] = X[perm[r] / k, :].
+ * Deterministic: no result depends on the order in which threads run.
+ *   M [V,E] int32 in [0,S);  slot, perm, inv_perm [P];  counts [S];  offsets [S+1];
+ *   Xg [P,d] dtype.  Uses `ws`.
+ */
+int mmoe_remap_permute(const mmoe_shape *shape, const void *X, const int32_t *vid,
+                       const int32_t *topk_idx, const int32_t *M, int32_t *slot, int32_t *counts,
+                       int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *Xg, void *ws,
+                       size_t ws_bytes, void *stream);
+
+/*
+ * Step F -- the resident experts applied to their groups (Algorithm 2,
+ * "expert[iL][iE](act)"; section 3.2: a Mixtral expert has 3*d*f parameters).
+ * For every slot s and row r in [offsets[s], offsets[s+1]):
+ *   SWIGLU: Yg[r,:] = (silu(Xg[r,:] W1[s]) * (Xg[r,:] W3[s])) W2[s],  silu(a) = a/(1+exp(-a))
+ *   RELU:   Yg[r,:] = relu(Xg[r,:] W1[s]) W2[s]
+ * Products accumulate in fp32; the hidden activation is stored in `dtype`
+ * (rounded to nearest even for bf16) between the two products.
+ *   Xg [P,d] dtype; offsets [S+1] int32 (device); W1p, W3p, W2p: PACKED pool
+ *   (see mmoe_pack_weights);  Yg [P,d] fp32 out.  Uses `ws` for the hidden activation.
+ */
+int mmoe_expert_ffn(const mmoe_shape *shape, const void *Xg, const int32_t *offsets,
+                    const void *W1p, const void *W3p, const void *W2p, float *Yg, void *ws,
+                    size_t ws_bytes, void *stream);
+
+/*
+ * Step C -- combination with the gate's coefficients (section 3.2):
+ *   Y[t,:] = sum_{j<k} topk_w[t,j] * Yg[inv_perm[t*k+j], :], fp32, ascending j,
+ * rounded once to `dtype`.  Gather-side: no atomics, deterministic.
+ *   Yg [P,d] fp32; inv_perm [P]; topk_w [T,k] fp32; Y [T,d] dtype out.
+ */
+int mmoe_combine(const mmoe_shape *shape, const float *Yg, const int32_t *inv_perm,
+                 const float *topk_w, void *Y, void *stream);
+
+/*
+ * The whole layer, R -> M -> G -> F -> C, on one stream with no host
+ * synchronisation; intermediates live in `ws`.  Arguments as above; the pool is
+ * the PACKED one.  Y [T,d] dtype out.
+ */
+int mmoe_layer_forward(const mmoe_shape *shape, const void *X, const int32_t *vid, const void *Wr,
+                       const float *br, const int32_t *M, const void *W1p, const void *W3p,
+                       const void *W2p, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Debugging aid, SYNCHRONISES the stream: checks on the device that every vid[t] is in
+ * [0,V) and every M[v][e] in [0,S).  Returns 0 if so, 1 if not, a negative status on
+ * argument errors.  `ws` needs 256 bytes.
+ */
+int mmoe_validate_inputs(const mmoe_shape *shape, const int32_t *vid, const int32_t *M, void *ws,
+                         size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMOE_H */

@@ -1,0 +1,207 @@
+// Step F, weight-streaming variant: the grouped expert FFN when a slot sees only a few
+// rows (decode-shaped batches) -- Algorithm 2, "expert[iL][iE](act)".  Each expert's
+// weights are then read from HBM exactly once and that read is the whole cost, so the
+// kernel is built around keeping many 16-byte loads of weights in flight per wavefront.
+//
+// Both products are of the form  out[r, n] = sum_k A[r, k] * W[s][n][k]  over the packed
+// (reduction-contiguous) pool.  A workgroup owns 16 output features n of one slot and all
+// rows of that slot; its four wavefronts split the reduction dimension and meet in LDS.
+// The 16 weight rows are the 16-row operand of a 16x16 matrix-core instruction and up to
+// 16 tokens are its 16 columns, so the weights pass through registers once however many
+// tokens (up to 32 per pass) the slot holds.
+//
+// Reduction-index permutation: per 256-byte step of a row, lane group g = lane/16 loads
+// the contiguous 64 bytes [64g, 64g+64) as four 16-byte pieces q; piece q of every group
+// feeds matrix instruction q.  Weights and activations use the same permutation, and a
+// sum does not care in which order its terms are visited, so no shuffle is needed and
+// every lane's global loads are contiguous.
+#include "mmoe_internal.h"
+
+namespace mmoe {
+
+enum { kModeReluH = 0, kModeSwigluH = 1, kModePlainF32 = 2 };
+
+constexpr int kSkThreads = 256;
+constexpr int kSkWaves = 4;
+constexpr int kSkMB = 2;  // 16-row token blocks per pass
+
+template <typename T> struct Mma;
+template <> struct Mma<uint16_t> {  // bf16, 16x16x32: one 16-byte piece = 8 reduction elements
+    static __device__ __forceinline__ f32x4 run(u32x4 w, u32x4 x, f32x4 acc)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x),
+                                                       acc, 0, 0, 0);
+    }
+};
+template <> struct Mma<float> {  // fp32, 16x16x4: one 16-byte piece = 4 elements = 4 instructions
+    static __device__ __forceinline__ f32x4 run(u32x4 w, u32x4 x, f32x4 acc)
+    {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(w[c]), __uint_as_float(x[c]), acc, 0, 0, 0);
+        return acc;
+    }
+};
+
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+
+template <typename T, int NW, int KU, int MODE>
+__global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict__ A,
+                                                            const int32_t* __restrict__ offsets,
+                                                            const T* __restrict__ W0, const T* __restrict__ W1,
+                                                            void* __restrict__ out, int K, int N)
+{
+    constexpr int EPB = 16 / (int)sizeof(T);  // elements per 16-byte piece
+    constexpr int KSS = 16 * EPB;             // elements per 256-byte step
+    __shared__ float red[kSkWaves][kSkMB][NW][kWave][4];
+
+    const int s = blockIdx.y;
+    const int n0 = blockIdx.x * 16;
+    const int r0 = offsets[s];
+    const int cnt = offsets[s + 1] - r0;
+    if (cnt <= 0) return;  // uniform over the workgroup
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int li = lane & 15, g = lane >> 4;
+    const int nit = K / (KSS * KU);
+
+    const T* wrow[NW];
+    wrow[0] = W0 + ((size_t)s * N + n0 + li) * K + g * (4 * EPB);
+    if (NW == 2) wrow[NW - 1] = W1 + ((size_t)s * N + n0 + li) * K + g * (4 * EPB);
+
+    for (int pass0 = 0; pass0 < cnt; pass0 += 16 * kSkMB) {
+        const int nmb = min(kSkMB, (cnt - pass0 + 15) / 16);
+        const T* arow[kSkMB];
+#pragma unroll
+        for (int mb = 0; mb < kSkMB; ++mb) {
+            int rr = min(pass0 + mb * 16 + li, cnt - 1);  // rows past the end re-read the last one; never stored
+            arow[mb] = A + (size_t)(r0 + rr) * K + g * (4 * EPB);
+        }
+        f32x4 acc[kSkMB][NW];
+#pragma unroll
+        for (int mb = 0; mb < kSkMB; ++mb)
+#pragma unroll
+            for (int w = 0; w < NW; ++w) acc[mb][w] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        u32x4 wcur[NW][KU][4], wnxt[NW][KU][4];
+        int it = wave;
+        if (it < nit) {
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int u = 0; u < KU; ++u)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        wcur[w][u][q] =
+                            *reinterpret_cast<const u32x4*>(wrow[w] + (size_t)(it * KU + u) * KSS + q * EPB);
+        }
+        for (; it < nit; it += kSkWaves) {
+            u32x4 xa[kSkMB][KU][4];
+#pragma unroll
+            for (int mb = 0; mb < kSkMB; ++mb)
+                if (mb < nmb) {
+#pragma unroll
+                    for (int u = 0; u < KU; ++u)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            xa[mb][u][q] =
+                                *reinterpret_cast<const u32x4*>(arow[mb] + (size_t)(it * KU + u) * KSS + q * EPB);
+                }
+            const int itn = it + kSkWaves;
+            if (itn < nit) {  // the next weights: the youngest loads, still in flight during the math below
+#pragma unroll
+                for (int w = 0; w < NW; ++w)
+#pragma unroll
+                    for (int u = 0; u < KU; ++u)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            wnxt[w][u][q] =
+                                *reinterpret_cast<const u32x4*>(wrow[w] + (size_t)(itn * KU + u) * KSS + q * EPB);
+            }
+#pragma unroll
+            for (int mb = 0; mb < kSkMB; ++mb)
+                if (mb < nmb) {
+#pragma unroll
+                    for (int u = 0; u < KU; ++u)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int w = 0; w < NW; ++w)
+                                acc[mb][w] = Mma<T>::run(wcur[w][u][q], xa[mb][u][q], acc[mb][w]);
+                }
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int u = 0; u < KU; ++u)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) wcur[w][u][q] = wnxt[w][u][q];
+        }
+
+#pragma unroll
+        for (int mb = 0; mb < kSkMB; ++mb)
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) red[wave][mb][w][lane][i] = acc[mb][w][i];
+        __syncthreads();
+        // accumulator element i of lane l is output feature n0 + 4*(l/16) + i of token column l%16
+        for (int idx = threadIdx.x; idx < nmb * kWave; idx += kSkThreads) {
+            const int mb = idx / kWave, l = idx % kWave;
+            const int row = pass0 + mb * 16 + (l & 15);
+            if (row < cnt) {
+                float v[NW][4];
+#pragma unroll
+                for (int w = 0; w < NW; ++w)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        v[w][i] = (red[0][mb][w][l][i] + red[1][mb][w][l][i]) + (red[2][mb][w][l][i] + red[3][mb][w][l][i]);
+                float o[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (MODE == kModeSwigluH) o[i] = silu_mul(v[0][i], v[NW - 1][i]);
+                    else if (MODE == kModeReluH) o[i] = fmaxf(v[0][i], 0.0f);
+                    else o[i] = v[0][i];
+                }
+                const size_t at = (size_t)(r0 + row) * N + n0 + 4 * (l >> 4);
+                if (MODE == kModePlainF32 || sizeof(T) == 4) {
+                    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = f32x4{o[0], o[1], o[2], o[3]};
+                } else {
+                    u32x2 pk;
+                    pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
+                    pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
+                    *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) = pk;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <typename T>
+static int run_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
+                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st)
+{
+    const int d = s.d_model, f = s.d_ff;
+    dim3 block(kSkThreads);
+    dim3 g1(f / 16, s.S), g2(d / 16, s.S);
+    const T* nul = nullptr;
+    if (s.act == MMOE_SWIGLU)
+        hipLaunchKernelGGL((skinny_kernel<T, 2, 1, kModeSwigluH>), g1, block, 0, st, (const T*)Xg, offsets,
+                           (const T*)W1p, (const T*)W3p, H, d, f);
+    else
+        hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH>), g1, block, 0, st, (const T*)Xg, offsets,
+                           (const T*)W1p, nul, H, d, f);
+    hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModePlainF32>), g2, block, 0, st, (const T*)H, offsets,
+                       (const T*)W2p, nul, (void*)Yg, f, d);
+    return launch_status();
+}
+
+int launch_ffn_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
+                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st)
+{
+    if (s.dtype == MMOE_BF16) return run_skinny<uint16_t>(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st);
+    return run_skinny<float>(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st);
+}
+
+}  // namespace mmoe

@@ -1,0 +1,215 @@
+// C-ABI entry points of libmmoe: argument checks, workspace carving, stage sequencing.
+// Every step of the layer runs in the HIP kernels of the other translation units.
+#include "mmoe_internal.h"
+
+namespace mmoe {
+
+int check_shape(const mmoe_shape* s)
+{
+    if (!s) return MMOE_ERR_NULL;
+    if (s->T <= 0 || s->d_model <= 0 || s->d_ff <= 0 || s->V <= 0 || s->E <= 0 || s->S <= 0 || s->top_k <= 0)
+        return MMOE_ERR_DIM;
+    if (s->dtype != MMOE_F32 && s->dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
+    if (s->act != MMOE_RELU && s->act != MMOE_SWIGLU) return MMOE_ERR_DTYPE;
+    if (s->top_k > s->E || s->top_k > kMaxTopK) return MMOE_ERR_TOPK;
+    if (s->d_model % 256 != 0 || s->d_ff % 256 != 0) return MMOE_ERR_MULTIPLE;
+    if (s->E > kMaxE || s->S > kMaxS) return MMOE_ERR_LIMIT;
+    int64_t P = (int64_t)s->T * s->top_k;
+    int64_t widest = s->d_model > s->d_ff ? s->d_model : s->d_ff;
+    if (P > (int64_t)1 << 30 || P * widest >= ((int64_t)1 << 35)) return MMOE_ERR_LIMIT;
+    return MMOE_OK;
+}
+
+WsLayout ws_layout(const mmoe_shape& s)
+{
+    WsLayout L;
+    size_t P = (size_t)s.T * s.top_k, es = elem_size(s.dtype);
+    L.nblk = (int)((P + kPermChunk - 1) / kPermChunk);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+    L.topk_idx = take(P * 4);
+    L.topk_w = take(P * 4);
+    L.slot = take(P * 4);
+    L.counts = take((size_t)s.S * 4);
+    L.offsets = take((size_t)(s.S + 1) * 4);
+    L.perm = take(P * 4);
+    L.inv_perm = take(P * 4);
+    L.blk_counts = take((size_t)L.nblk * s.S * 4);
+    L.blk_base = take((size_t)L.nblk * s.S * 4);
+    L.Xg = take(P * s.d_model * es);
+    L.H = take(P * s.d_ff * es);
+    L.Yg = take(P * s.d_model * 4);
+    L.total = off;
+    return L;
+}
+
+bool use_skinny(const mmoe_shape& s)
+{
+    // fp32 always streams (fp32 MFMA, full precision).  bf16 streams when a slot sees few
+    // rows on average: the weights are then read once from HBM and that read is the bound.
+    if (s.dtype == MMOE_F32) return true;
+    int64_t P = (int64_t)s.T * s.top_k;
+    return P <= (int64_t)48 * s.S;
+}
+
+static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+}  // namespace mmoe
+
+using namespace mmoe;
+
+extern "C" {
+
+size_t mmoe_workspace_bytes(const mmoe_shape* shape)
+{
+    if (check_shape(shape) != MMOE_OK) return 0;
+    return ws_layout(*shape).total;
+}
+
+const char* mmoe_strerror(int status)
+{
+    switch (status) {
+        case MMOE_OK: return "success";
+        case MMOE_ERR_NULL: return "a required pointer is NULL";
+        case MMOE_ERR_DIM: return "a dimension is not positive";
+        case MMOE_ERR_TOPK: return "top_k exceeds E or the supported maximum of 8";
+        case MMOE_ERR_DTYPE: return "unknown dtype or activation";
+        case MMOE_ERR_W3: return "W3 must be given for SWIGLU and must be NULL for RELU";
+        case MMOE_ERR_WORKSPACE: return "workspace missing or smaller than mmoe_workspace_bytes()";
+        case MMOE_ERR_ALIGN: return "a pointer is not sufficiently aligned (16 bytes; workspace 256)";
+        case MMOE_ERR_MULTIPLE: return "d_model and d_ff must be multiples of 256";
+        case MMOE_ERR_LIMIT: return "E, S or the problem size exceeds the library's limits";
+        case MMOE_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+        default: return "unknown status";
+    }
+}
+
+int mmoe_pack_weights(const mmoe_shape* shape, const void* W1, const void* W3, const void* W2, void* W1p,
+                      void* W3p, void* W2p, void* stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!W1 || !W2 || !W1p || !W2p) return MMOE_ERR_NULL;
+    bool gated = shape->act == MMOE_SWIGLU;
+    if (gated != (W3 != nullptr) || gated != (W3p != nullptr)) return MMOE_ERR_W3;
+    if (misaligned(W1, 16) || misaligned(W2, 16) || misaligned(W3, 16) || misaligned(W1p, 16) ||
+        misaligned(W2p, 16) || misaligned(W3p, 16))
+        return MMOE_ERR_ALIGN;
+    return launch_pack(*shape, W1, W3, W2, W1p, W3p, W2p, (hipStream_t)stream);
+}
+
+int mmoe_route(const mmoe_shape* shape, const void* X, const int32_t* vid, const void* Wr, const float* br,
+               int32_t* topk_idx, float* topk_w, void* stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!X || !vid || !Wr || !topk_idx || !topk_w) return MMOE_ERR_NULL;
+    if (misaligned(X, 16) || misaligned(Wr, 16) || misaligned(vid, 4) || misaligned(br, 4) ||
+        misaligned(topk_idx, 4) || misaligned(topk_w, 4))
+        return MMOE_ERR_ALIGN;
+    return launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, (hipStream_t)stream);
+}
+
+int mmoe_remap_permute(const mmoe_shape* shape, const void* X, const int32_t* vid, const int32_t* topk_idx,
+                       const int32_t* M, int32_t* slot, int32_t* counts, int32_t* offsets, int32_t* perm,
+                       int32_t* inv_perm, void* Xg, void* ws, size_t ws_bytes, void* stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!X || !vid || !topk_idx || !M || !slot || !counts || !offsets || !perm || !inv_perm || !Xg)
+        return MMOE_ERR_NULL;
+    WsLayout L = ws_layout(*shape);
+    size_t need = 2 * align256((size_t)L.nblk * shape->S * 4);
+    if (!ws || ws_bytes < need) return MMOE_ERR_WORKSPACE;
+    if (misaligned(ws, 256) || misaligned(X, 16) || misaligned(Xg, 16) || misaligned(vid, 4) ||
+        misaligned(topk_idx, 4) || misaligned(M, 4) || misaligned(slot, 4) || misaligned(counts, 4) ||
+        misaligned(offsets, 4) || misaligned(perm, 4) || misaligned(inv_perm, 4))
+        return MMOE_ERR_ALIGN;
+    int32_t* blk_counts = (int32_t*)ws;
+    int32_t* blk_base = (int32_t*)((char*)ws + need / 2);
+    return launch_permute(*shape, X, vid, topk_idx, M, slot, counts, offsets, perm, inv_perm, Xg, blk_counts,
+                          blk_base, L.nblk, (hipStream_t)stream);
+}
+
+int mmoe_expert_ffn(const mmoe_shape* shape, const void* Xg, const int32_t* offsets, const void* W1p,
+                    const void* W3p, const void* W2p, float* Yg, void* ws, size_t ws_bytes, void* stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!Xg || !offsets || !W1p || !W2p || !Yg) return MMOE_ERR_NULL;
+    if ((shape->act == MMOE_SWIGLU) != (W3p != nullptr)) return MMOE_ERR_W3;
+    size_t need = (size_t)shape->T * shape->top_k * shape->d_ff * elem_size(shape->dtype);
+    if (!ws || ws_bytes < need) return MMOE_ERR_WORKSPACE;
+    if (misaligned(ws, 256) || misaligned(Xg, 16) || misaligned(W1p, 16) || misaligned(W3p, 16) ||
+        misaligned(W2p, 16) || misaligned(Yg, 16) || misaligned(offsets, 4))
+        return MMOE_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    if (use_skinny(*shape)) return launch_ffn_skinny(*shape, Xg, offsets, W1p, W3p, W2p, ws, Yg, st);
+    return launch_ffn_tiled(*shape, Xg, offsets, W1p, W3p, W2p, ws, Yg, st);
+}
+
+int mmoe_combine(const mmoe_shape* shape, const float* Yg, const int32_t* inv_perm, const float* topk_w,
+                 void* Y, void* stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!Yg || !inv_perm || !topk_w || !Y) return MMOE_ERR_NULL;
+    if (misaligned(Yg, 16) || misaligned(Y, 16) || misaligned(inv_perm, 4) || misaligned(topk_w, 4))
+        return MMOE_ERR_ALIGN;
+    return launch_combine(*shape, Yg, inv_perm, topk_w, Y, (hipStream_t)stream);
+}
+
+int mmoe_layer_forward(const mmoe_shape* shape, const void* X, const int32_t* vid, const void* Wr,
+                       const float* br, const int32_t* M, const void* W1p, const void* W3p, const void* W2p,
+                       void* Y, void* ws, size_t ws_bytes, void* stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!X || !vid || !Wr || !M || !W1p || !W2p || !Y) return MMOE_ERR_NULL;
+    if ((shape->act == MMOE_SWIGLU) != (W3p != nullptr)) return MMOE_ERR_W3;
+    WsLayout L = ws_layout(*shape);
+    if (!ws || ws_bytes < L.total) return MMOE_ERR_WORKSPACE;
+    if (misaligned(ws, 256) || misaligned(X, 16) || misaligned(Wr, 16) || misaligned(W1p, 16) ||
+        misaligned(W3p, 16) || misaligned(W2p, 16) || misaligned(Y, 16) || misaligned(vid, 4) ||
+        misaligned(br, 4) || misaligned(M, 4))
+        return MMOE_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    char* w = (char*)ws;
+    int32_t* topk_idx = (int32_t*)(w + L.topk_idx);
+    float* topk_w = (float*)(w + L.topk_w);
+    int32_t* offsets = (int32_t*)(w + L.offsets);
+    int32_t* inv_perm = (int32_t*)(w + L.inv_perm);
+    float* Yg = (float*)(w + L.Yg);
+
+    rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st);
+    if (rc) return rc;
+    rc = launch_permute(*shape, X, vid, topk_idx, M, (int32_t*)(w + L.slot), (int32_t*)(w + L.counts), offsets,
+                        (int32_t*)(w + L.perm), inv_perm, w + L.Xg, (int32_t*)(w + L.blk_counts),
+                        (int32_t*)(w + L.blk_base), L.nblk, st);
+    if (rc) return rc;
+    if (use_skinny(*shape))
+        rc = launch_ffn_skinny(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, st);
+    else
+        rc = launch_ffn_tiled(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, st);
+    if (rc) return rc;
+    return launch_combine(*shape, Yg, inv_perm, topk_w, Y, st);
+}
+
+int mmoe_validate_inputs(const mmoe_shape* shape, const int32_t* vid, const int32_t* M, void* ws,
+                         size_t ws_bytes, void* stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!vid || !M) return MMOE_ERR_NULL;
+    if (!ws || ws_bytes < 256) return MMOE_ERR_WORKSPACE;
+    if (misaligned(ws, 256)) return MMOE_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    rc = launch_validate(*shape, vid, M, (int32_t*)ws, st);
+    if (rc) return rc;
+    int32_t flag = 0;
+    if (hipMemcpyAsync(&flag, ws, 4, hipMemcpyDeviceToHost, st) != hipSuccess) return MMOE_ERR_LAUNCH;
+    if (hipStreamSynchronize(st) != hipSuccess) return MMOE_ERR_LAUNCH;
+    return flag ? 1 : 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,72 @@
+// Internal declarations shared by the HIP translation units of libmmoe (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "mmoe.h"
+
+namespace mmoe {
+
+constexpr int kWave = 64;
+constexpr int kMaxTopK = 8;
+constexpr int kMaxE = 256;
+constexpr int kMaxS = 1024;
+constexpr int kPermChunk = 2048;  // pairs per workgroup in the grouping kernels
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// fp32 -> bf16, round to nearest even (hardware conversion on gfx950)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x)
+{
+    bf16_t h = (bf16_t)x;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline size_t elem_size(int dtype) { return dtype == MMOE_BF16 ? 2 : 4; }
+
+// Sub-buffers of the caller's workspace used by mmoe_layer_forward (byte offsets).
+struct WsLayout {
+    size_t topk_idx, topk_w, slot, counts, offsets, perm, inv_perm, blk_counts, blk_base, Xg, H, Yg, total;
+    int nblk;
+};
+WsLayout ws_layout(const mmoe_shape& s);
+
+int check_shape(const mmoe_shape* s);
+
+// true when the expert stage uses the weight-streaming kernels (few rows per slot)
+bool use_skinny(const mmoe_shape& s);
+
+// Kernel launchers (one per translation unit).  All return an mmoe_status.
+int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const void* Wr, const float* br,
+                 int32_t* topk_idx, float* topk_w, hipStream_t st);
+int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const int32_t* topk_idx,
+                   const int32_t* M, int32_t* slot, int32_t* counts, int32_t* offsets, int32_t* perm,
+                   int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk,
+                   hipStream_t st);
+int launch_ffn_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
+                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st);
+int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
+                     const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st);
+int launch_combine(const mmoe_shape& s, const float* Yg, const int32_t* inv_perm, const float* topk_w,
+                   void* Y, hipStream_t st);
+int launch_pack(const mmoe_shape& s, const void* W1, const void* W3, const void* W2, void* W1p, void* W3p,
+                void* W2p, hipStream_t st);
+int launch_validate(const mmoe_shape& s, const int32_t* vid, const int32_t* M, int32_t* flag, hipStream_t st);
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? MMOE_OK : MMOE_ERR_LAUNCH;
+}
+
+}  // namespace mmoe

@@ -1,0 +1,194 @@
+// Steps M and G: expert-map lookup, slot histogram, exclusive scan, stable grouping of
+// the (token, pick) pairs by pool slot, and the row gather (Algorithm 2, the map lookup
+// that precedes the expert call; grouping is what lets one resident expert serve every
+// token that hit it, whichever variant the token belongs to).
+//
+// Deterministic by construction: the rank of pair p inside its slot is the number of
+// lower pair ids with the same slot, computed from wavefront ballots and integer
+// prefix sums.  There are no cursors bumped by atomics and no waiting between
+// workgroups: three short kernels (histogram, scan, scatter) and one gather.
+//
+// Work split: workgroup b owns pairs [b*2048, (b+1)*2048); inside it wavefront w owns a
+// contiguous quarter, walked 64 pairs at a time in ascending order.
+#include "mmoe_internal.h"
+
+namespace mmoe {
+
+constexpr int kPermThreads = 256;
+constexpr int kPermWaves = kPermThreads / kWave;
+constexpr int kPairsPerWave = kPermChunk / kPermWaves;  // 512
+
+// slot[p] = M[vid[p / k]][topk_idx[p]]; per-workgroup histogram of the slots.
+__global__ __launch_bounds__(kPermThreads) void slot_hist_kernel(
+    const int32_t* __restrict__ vid, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ M,
+    int32_t* __restrict__ slot, int32_t* __restrict__ blk_counts, int P, int k, int V, int E, int S)
+{
+    __shared__ int hist[kMaxS];
+    for (int s = threadIdx.x; s < S; s += kPermThreads) hist[s] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * kPermChunk;
+    for (int i = threadIdx.x; i < kPermChunk; i += kPermThreads) {
+        int p = base + i;
+        if (p < P) {
+            // clamps keep every later index in range even for invalid ids (results then undefined)
+            int v = min(max(vid[p / k], 0), V - 1);
+            int e = min(max(topk_idx[p], 0), E - 1);
+            int s = min(max(M[v * E + e], 0), S - 1);
+            slot[p] = s;
+            atomicAdd(&hist[s], 1);  // integer LDS atomic: the sum does not depend on order
+        }
+    }
+    __syncthreads();
+    for (int s = threadIdx.x; s < S; s += kPermThreads) blk_counts[(size_t)blockIdx.x * S + s] = hist[s];
+}
+
+// counts, offsets, and for every (workgroup, slot) the first output row of that workgroup's pairs.
+__global__ __launch_bounds__(kPermThreads) void slot_scan_kernel(const int32_t* __restrict__ blk_counts,
+                                                                 int32_t* __restrict__ blk_base,
+                                                                 int32_t* __restrict__ counts,
+                                                                 int32_t* __restrict__ offsets, int nblk, int S)
+{
+    __shared__ int tot[kMaxS];
+    __shared__ int off[kMaxS + 1];
+    for (int s = threadIdx.x; s < S; s += kPermThreads) {
+        int run = 0;
+        for (int b = 0; b < nblk; ++b) {
+            int c = blk_counts[(size_t)b * S + s];
+            blk_base[(size_t)b * S + s] = run;
+            run += c;
+        }
+        tot[s] = run;
+        counts[s] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x < kWave) {  // one wavefront scans the S totals, 64 at a time
+        int carry = 0;
+        for (int s0 = 0; s0 < S; s0 += kWave) {
+            int s = s0 + threadIdx.x;
+            int c = s < S ? tot[s] : 0;
+            int incl = c;
+#pragma unroll
+            for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+                int o = __shfl_up(incl, dlt, kWave);
+                if ((int)threadIdx.x >= dlt) incl += o;
+            }
+            if (s < S) off[s] = carry + incl - c;
+            carry += __shfl(incl, kWave - 1, kWave);
+        }
+        if (threadIdx.x == 0) off[S] = carry;
+    }
+    __syncthreads();
+    for (int s = threadIdx.x; s <= S; s += kPermThreads) offsets[s] = off[s];
+    for (int s = threadIdx.x; s < S; s += kPermThreads) {
+        int o = off[s];
+        for (int b = 0; b < nblk; ++b) blk_base[(size_t)b * S + s] += o;
+    }
+}
+
+// perm / inv_perm: stable ranks from ballots.
+__global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_t* __restrict__ slot,
+                                                                    const int32_t* __restrict__ blk_base,
+                                                                    int32_t* __restrict__ perm,
+                                                                    int32_t* __restrict__ inv_perm, int P, int S)
+{
+    __shared__ int wtot[kPermWaves][kMaxS];  // pairs of each slot owned by each wavefront
+    __shared__ int cursor[kPermWaves][kMaxS];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    for (int i = threadIdx.x; i < kPermWaves * S; i += kPermThreads) wtot[i / S][i % S] = 0;
+    __syncthreads();
+    const int wbase = blockIdx.x * kPermChunk + wave * kPairsPerWave;
+    for (int i = lane; i < kPairsPerWave; i += kWave) {
+        int p = wbase + i;
+        if (p < P) atomicAdd(&wtot[wave][slot[p]], 1);
+    }
+    __syncthreads();
+    for (int s = threadIdx.x; s < S; s += kPermThreads) {
+        int run = blk_base[(size_t)blockIdx.x * S + s];
+#pragma unroll
+        for (int w = 0; w < kPermWaves; ++w) {
+            cursor[w][s] = run;
+            run += wtot[w][s];
+        }
+    }
+    __syncthreads();
+    // From here on a wavefront touches only its own cursor row; LDS operations of one
+    // wavefront execute in program order.
+    volatile int* cur = cursor[wave];
+    for (int i0 = 0; i0 < kPairsPerWave; i0 += kWave) {
+        int p = wbase + i0 + lane;
+        bool valid = p < P;
+        int s = valid ? slot[p] : -1;
+        unsigned long long todo = __ballot(valid);
+        while (todo) {
+            int leader = __ffsll((long long)todo) - 1;
+            int s0 = __shfl(s, leader, kWave);
+            unsigned long long m = __ballot(valid && s == s0);
+            if (valid && s == s0) {
+                int rank = __popcll(m & ((1ull << lane) - 1ull));
+                int r = cur[s0] + rank;
+                perm[r] = p;
+                inv_perm[p] = r;
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane == leader) cur[s0] = cur[s0] + __popcll(m);
+            __builtin_amdgcn_wave_barrier();
+            todo &= ~m;
+        }
+    }
+}
+
+// Xg[r,:] = X[perm[r] / k, :], one wavefront per row, 16 bytes per lane per step.
+__global__ __launch_bounds__(kPermThreads) void gather_rows_kernel(const u32x4* __restrict__ X,
+                                                                   const int32_t* __restrict__ perm,
+                                                                   u32x4* __restrict__ Xg, int P, int k,
+                                                                   int row_vec)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int r = blockIdx.x * kPermWaves + threadIdx.x / kWave;
+    if (r >= P) return;
+    const int t = perm[r] / k;
+    const u32x4* src = X + (size_t)t * row_vec;
+    u32x4* dst = Xg + (size_t)r * row_vec;
+    for (int i = lane; i < row_vec; i += kWave) dst[i] = src[i];
+}
+
+__global__ void validate_kernel(const int32_t* __restrict__ vid, const int32_t* __restrict__ M,
+                                int32_t* __restrict__ flag, int T, int V, int E, int S)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    bool bad = false;
+    if (i < T) bad = vid[i] < 0 || vid[i] >= V;
+    if (i < V * E) bad = bad || M[i] < 0 || M[i] >= S;
+    if (bad) atomicOr(flag, 1);
+}
+
+__global__ void clear_flag_kernel(int32_t* flag) { *flag = 0; }
+
+int launch_validate(const mmoe_shape& s, const int32_t* vid, const int32_t* M, int32_t* flag, hipStream_t st)
+{
+    int n = s.T > s.V * s.E ? s.T : s.V * s.E;
+    hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, st, flag);
+    hipLaunchKernelGGL(validate_kernel, dim3((n + 255) / 256), dim3(256), 0, st, vid, M, flag, s.T, s.V, s.E,
+                       s.S);
+    return launch_status();
+}
+
+int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const int32_t* topk_idx,
+                   const int32_t* M, int32_t* slot, int32_t* counts, int32_t* offsets, int32_t* perm,
+                   int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk, hipStream_t st)
+{
+    const int P = s.T * s.top_k;
+    hipLaunchKernelGGL(slot_hist_kernel, dim3(nblk), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot,
+                       blk_counts, P, s.top_k, s.V, s.E, s.S);
+    hipLaunchKernelGGL(slot_scan_kernel, dim3(1), dim3(kPermThreads), 0, st, blk_counts, blk_base, counts,
+                       offsets, nblk, s.S);
+    hipLaunchKernelGGL(slot_scatter_kernel, dim3(nblk), dim3(kPermThreads), 0, st, slot, blk_base, perm,
+                       inv_perm, P, s.S);
+    const int row_vec = (int)((size_t)s.d_model * elem_size(s.dtype) / 16);
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((P + kPermWaves - 1) / kPermWaves), dim3(kPermThreads), 0, st,
+                       (const u32x4*)X, perm, (u32x4*)Xg, P, s.top_k, row_vec);
+    return launch_status();
+}
+
+}  // namespace mmoe

@@ -1,0 +1,158 @@
+// Step R: per-variant gate, top-k selection and coefficients (Algorithm 2, "gate(act)";
+// section 3.2).  One wavefront scores one token.
+//
+// The logit is an fp32 sum in the fixed order the header states: lane l owns the
+// elements i with (i div 4) mod 64 == l, which is exactly what a coalesced 4-element
+// vector load per lane delivers; each lane folds its elements in ascending i with one
+// fused multiply-add each; the 64 partial sums meet in an xor butterfly 32,16,...,1.
+// fp32 addition is commutative, so both partners of an exchange compute the same sum and
+// every lane ends with the same value.
+//
+// Logits are parked in LDS, then the k winners are found by wavefront arg-max
+// reductions: lane l looks after experts l, l+64, ...; ties go to the lower index.
+#include "mmoe_internal.h"
+
+namespace mmoe {
+
+constexpr int kRouteWaves = 4;   // tokens per workgroup
+constexpr int kEC = 8;           // experts scored per sweep over the token
+
+template <typename T> struct Vec4;
+template <> struct Vec4<float> {
+    static __device__ __forceinline__ void load(const float* p, float (&v)[4])
+    {
+        f32x4 t = *reinterpret_cast<const f32x4*>(p);
+        v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+    }
+};
+template <> struct Vec4<uint16_t> {
+    static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[4])
+    {
+        u32x2 t = *reinterpret_cast<const u32x2*>(p);
+        v[0] = __uint_as_float(t[0] << 16);
+        v[1] = __uint_as_float(t[0] & 0xFFFF0000u);
+        v[2] = __uint_as_float(t[1] << 16);
+        v[3] = __uint_as_float(t[1] & 0xFFFF0000u);
+    }
+};
+
+template <typename T>
+__global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
+    const T* __restrict__ X, const int32_t* __restrict__ vid, const T* __restrict__ Wr,
+    const float* __restrict__ br, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d,
+    int V, int E, int k)
+{
+    __shared__ float lds_logit[kRouteWaves][kMaxE];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int t = blockIdx.x * kRouteWaves + wave;
+    if (t >= Tn) return;  // whole wavefront leaves; no workgroup barrier below
+
+    const int v = min(max(vid[t], 0), V - 1);  // out-of-range ids are the caller's error; stay in bounds
+    const T* x = X + (size_t)t * d;
+    const T* wv = Wr + (size_t)v * E * d;
+    const int nvec = d / 4;  // d is a multiple of 256
+
+    for (int e0 = 0; e0 < E; e0 += kEC) {
+        float acc[kEC];
+#pragma unroll
+        for (int c = 0; c < kEC; ++c) acc[c] = 0.0f;
+        for (int q = lane; q < nvec; q += kWave) {  // ascending i within the lane
+            float xv[4];
+            Vec4<T>::load(x + 4 * q, xv);
+#pragma unroll
+            for (int c = 0; c < kEC; ++c) {
+                if (e0 + c < E) {
+                    float wvv[4];
+                    Vec4<T>::load(wv + (size_t)(e0 + c) * d + 4 * q, wvv);
+                    acc[c] = __builtin_fmaf(xv[0], wvv[0], acc[c]);
+                    acc[c] = __builtin_fmaf(xv[1], wvv[1], acc[c]);
+                    acc[c] = __builtin_fmaf(xv[2], wvv[2], acc[c]);
+                    acc[c] = __builtin_fmaf(xv[3], wvv[3], acc[c]);
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < kEC; ++c) {
+            float p = acc[c];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) p = p + __shfl_xor(p, off, kWave);
+            if (e0 + c < E) {
+                if (br) p = p + br[(size_t)v * E + e0 + c];
+                if (lane == 0) lds_logit[wave][e0 + c] = p;
+            }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // each lane looks after experts lane, lane+64, lane+128, lane+192
+    constexpr int kPerLane = kMaxE / kWave;
+    float mine[kPerLane];
+#pragma unroll
+    for (int q = 0; q < kPerLane; ++q) {
+        int e = lane + q * kWave;
+        mine[q] = e < E ? lds_logit[wave][e] : -INFINITY;
+    }
+    uint32_t taken = 0;
+    float sel[kMaxTopK];
+    int seli[kMaxTopK];
+#pragma unroll
+    for (int j = 0; j < kMaxTopK; ++j) {
+        if (j < k) {
+            float bv = -INFINITY;
+            int be = 0x7FFFFFFF;
+#pragma unroll
+            for (int q = 0; q < kPerLane; ++q) {  // ascending index: strict > keeps the lower one
+                int e = lane + q * kWave;
+                if (e < E && !(taken & (1u << q)) && (be == 0x7FFFFFFF || mine[q] > bv)) {
+                    bv = mine[q];
+                    be = e;
+                }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                float ov = __shfl_xor(bv, off, kWave);
+                int oe = __shfl_xor(be, off, kWave);
+                bool other_valid = oe != 0x7FFFFFFF, self_valid = be != 0x7FFFFFFF;
+                bool take = other_valid && (!self_valid || ov > bv || (ov == bv && oe < be));
+                if (take) { bv = ov; be = oe; }
+            }
+            sel[j] = bv;
+            seli[j] = be;
+            if ((be & (kWave - 1)) == lane) taken |= 1u << (be / kWave);
+        }
+    }
+    if (lane == 0) {
+        float z[kMaxTopK];
+        float tot = 0.0f;
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j)
+            if (j < k) {
+                z[j] = expf(sel[j] - sel[0]);
+                tot += z[j];
+            }
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j)
+            if (j < k) {
+                topk_idx[(size_t)t * k + j] = seli[j];
+                topk_w[(size_t)t * k + j] = z[j] / tot;
+            }
+    }
+}
+
+int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const void* Wr, const float* br,
+                 int32_t* topk_idx, float* topk_w, hipStream_t st)
+{
+    dim3 grid((s.T + kRouteWaves - 1) / kRouteWaves), block(kRouteWaves * kWave);
+    if (s.dtype == MMOE_BF16)
+        hipLaunchKernelGGL(route_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)X, vid,
+                           (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k);
+    else
+        hipLaunchKernelGGL(route_kernel<float>, grid, block, 0, st, (const float*)X, vid, (const float*)Wr, br,
+                           topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k);
+    return launch_status();
+}
+
+}  // namespace mmoe

@@ -1,0 +1,205 @@
+"""Python binding of libmmoe's C ABI (see include/mmoe.h).
+
+Argument marshalling only: tensors are checked for device, dtype and contiguity, their
+raw device pointers and the current HIP stream are handed to the library, and every
+step of the layer runs in the library's kernels.  PyTorch supplies device memory and
+streams, nothing else.  There is no fallback: if the HIP library is missing the import
+of a function fails with an explanation.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmmoe.so")
+
+F32, BF16 = 0, 1
+RELU, SWIGLU = 0, 1
+_DTYPES = {"f32": F32, "bf16": BF16}
+_ACTS = {"relu": RELU, "swiglu": SWIGLU}
+_TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
+
+EXPORTS = [
+    "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
+    "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_validate_inputs",
+]
+
+
+class MmoeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("T", "d_model", "d_ff", "V", "E", "S", "top_k", "dtype", "act")]
+
+
+def make_shape(T, d_model, d_ff, V, E, S, top_k, dtype, act) -> Shape:
+    dt = _DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
+    ac = _ACTS[act] if isinstance(act, str) else int(act)
+    return Shape(T, d_model, d_ff, V, E, S, top_k, dt, ac)
+
+
+_lib = None
+
+
+def lib():
+    """Load libmmoe.so (built in-tree by ``__graft_entry__.build()`` / ``build.py``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2505_06481_amd.build` "
+                "(hipcc, gfx950).  There is no CPU fallback.")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, sz, i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        sp = ctypes.POINTER(Shape)
+        L.mmoe_workspace_bytes.restype = sz
+        L.mmoe_workspace_bytes.argtypes = [sp]
+        L.mmoe_strerror.restype = ctypes.c_char_p
+        L.mmoe_strerror.argtypes = [i]
+        L.mmoe_pack_weights.argtypes = [sp] + [vp] * 7
+        L.mmoe_route.argtypes = [sp] + [vp] * 7
+        L.mmoe_remap_permute.argtypes = [sp] + [vp] * 11 + [sz, vp]
+        L.mmoe_expert_ffn.argtypes = [sp] + [vp] * 7 + [sz, vp]
+        L.mmoe_combine.argtypes = [sp] + [vp] * 5
+        L.mmoe_layer_forward.argtypes = [sp] + [vp] * 10 + [sz, vp]
+        L.mmoe_validate_inputs.argtypes = [sp, vp, vp, vp, sz, vp]
+        for n in EXPORTS[2:]:
+            getattr(L, n).restype = i
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().mmoe_strerror(int(status)).decode()
+
+
+def workspace_bytes(shape: Shape) -> int:
+    return int(lib().mmoe_workspace_bytes(ctypes.byref(shape)))
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, numel=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name}: needs {numel} elements, has {t.numel()}")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise MmoeError(rc, where)
+
+
+def alloc_workspace(shape: Shape, device="cuda") -> torch.Tensor:
+    n = workspace_bytes(shape)
+    if n == 0:
+        raise MmoeError(int(lib().mmoe_route(ctypes.byref(shape), *([None] * 7))), "mmoe_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def pack_weights(shape: Shape, W1, W3, W2):
+    """Plain [S,d,f]/[S,f,d] pool -> packed [S,f,d]/[S,d,f] pool (new tensors)."""
+    dt = _TORCH_DT[shape.dtype]
+    S, d, f = shape.S, shape.d_model, shape.d_ff
+    W1p = torch.empty((S, f, d), dtype=dt, device=W1.device)
+    W2p = torch.empty((S, d, f), dtype=dt, device=W1.device)
+    W3p = torch.empty((S, f, d), dtype=dt, device=W1.device) if W3 is not None else None
+    rc = lib().mmoe_pack_weights(ctypes.byref(shape), _ptr(W1, dt, S * d * f, "W1"), _ptr(W3, dt, S * d * f, "W3"),
+                                 _ptr(W2, dt, S * d * f, "W2"), _ptr(W1p), _ptr(W3p), _ptr(W2p), _stream())
+    _check(rc, "mmoe_pack_weights")
+    return W1p, W3p, W2p
+
+
+def route(shape: Shape, X, vid, Wr, br=None):
+    dt = _TORCH_DT[shape.dtype]
+    T, k = shape.T, shape.top_k
+    idx = torch.empty((T, k), dtype=torch.int32, device=X.device)
+    w = torch.empty((T, k), dtype=torch.float32, device=X.device)
+    rc = lib().mmoe_route(ctypes.byref(shape), _ptr(X, dt, T * shape.d_model, "X"), _ptr(vid, torch.int32, T, "vid"),
+                          _ptr(Wr, dt, shape.V * shape.E * shape.d_model, "Wr"),
+                          _ptr(br, torch.float32, shape.V * shape.E, "br"), _ptr(idx), _ptr(w), _stream())
+    _check(rc, "mmoe_route")
+    return idx, w
+
+
+def remap_permute(shape: Shape, X, vid, topk_idx, M, ws):
+    dt = _TORCH_DT[shape.dtype]
+    P, S = shape.T * shape.top_k, shape.S
+    dev = X.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    slot, perm, inv = (torch.empty(P, **i32) for _ in range(3))
+    counts, offsets = torch.empty(S, **i32), torch.empty(S + 1, **i32)
+    Xg = torch.empty((P, shape.d_model), dtype=dt, device=dev)
+    rc = lib().mmoe_remap_permute(ctypes.byref(shape), _ptr(X, dt, shape.T * shape.d_model, "X"),
+                                  _ptr(vid, torch.int32, shape.T, "vid"), _ptr(topk_idx, torch.int32, P, "topk_idx"),
+                                  _ptr(M, torch.int32, shape.V * shape.E, "M"), _ptr(slot), _ptr(counts),
+                                  _ptr(offsets), _ptr(perm), _ptr(inv), _ptr(Xg), _ptr(ws, torch.uint8, None, "ws"),
+                                  ws.numel(), _stream())
+    _check(rc, "mmoe_remap_permute")
+    return slot, counts, offsets, perm, inv, Xg
+
+
+def expert_ffn(shape: Shape, Xg, offsets, W1p, W3p, W2p, ws):
+    dt = _TORCH_DT[shape.dtype]
+    P, d, f, S = shape.T * shape.top_k, shape.d_model, shape.d_ff, shape.S
+    Yg = torch.empty((P, d), dtype=torch.float32, device=Xg.device)
+    rc = lib().mmoe_expert_ffn(ctypes.byref(shape), _ptr(Xg, dt, P * d, "Xg"),
+                               _ptr(offsets, torch.int32, S + 1, "offsets"), _ptr(W1p, dt, S * d * f, "W1p"),
+                               _ptr(W3p, dt, S * d * f, "W3p"), _ptr(W2p, dt, S * d * f, "W2p"), _ptr(Yg),
+                               _ptr(ws, torch.uint8, None, "ws"), ws.numel(), _stream())
+    _check(rc, "mmoe_expert_ffn")
+    return Yg
+
+
+def combine(shape: Shape, Yg, inv_perm, topk_w):
+    dt = _TORCH_DT[shape.dtype]
+    P = shape.T * shape.top_k
+    Y = torch.empty((shape.T, shape.d_model), dtype=dt, device=Yg.device)
+    rc = lib().mmoe_combine(ctypes.byref(shape), _ptr(Yg, torch.float32, P * shape.d_model, "Yg"),
+                            _ptr(inv_perm, torch.int32, P, "inv_perm"), _ptr(topk_w, torch.float32, P, "topk_w"),
+                            _ptr(Y), _stream())
+    _check(rc, "mmoe_combine")
+    return Y
+
+
+def layer_forward(shape: Shape, X, vid, Wr, br, M, W1p, W3p, W2p, ws, Y=None):
+    dt = _TORCH_DT[shape.dtype]
+    S, d, f = shape.S, shape.d_model, shape.d_ff
+    if Y is None:
+        Y = torch.empty((shape.T, d), dtype=dt, device=X.device)
+    rc = lib().mmoe_layer_forward(ctypes.byref(shape), _ptr(X, dt, shape.T * d, "X"),
+                                  _ptr(vid, torch.int32, shape.T, "vid"), _ptr(Wr, dt, shape.V * shape.E * d, "Wr"),
+                                  _ptr(br, torch.float32, shape.V * shape.E, "br"),
+                                  _ptr(M, torch.int32, shape.V * shape.E, "M"), _ptr(W1p, dt, S * d * f, "W1p"),
+                                  _ptr(W3p, dt, S * d * f, "W3p"), _ptr(W2p, dt, S * d * f, "W2p"),
+                                  _ptr(Y, dt, shape.T * d, "Y"), _ptr(ws, torch.uint8, None, "ws"), ws.numel(),
+                                  _stream())
+    _check(rc, "mmoe_layer_forward")
+    return Y
+
+
+def validate_inputs(shape: Shape, vid, M, ws) -> bool:
+    rc = lib().mmoe_validate_inputs(ctypes.byref(shape), _ptr(vid, torch.int32, shape.T, "vid"),
+                                    _ptr(M, torch.int32, shape.V * shape.E, "M"), _ptr(ws, torch.uint8, 256, "ws"),
+                                    ws.numel(), _stream())
+    if rc < 0:
+        raise MmoeError(rc, "mmoe_validate_inputs")
+    return rc == 0

@@ -1,0 +1,176 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs.  Integer outputs (selected experts, slots, histogram, offsets,
+permutation, gathered rows) must match bit for bit; floating-point outputs within
+
+    bf16 storage:  |got - ref| <= 1e-2 + 2e-2 |ref|
+    fp32 storage:  |got - ref| <= 1e-4 |ref| + 1e-4 rms(ref)
+
+Small cases compare every element; the full benchmark shapes compare every integer output
+and a seeded sample of output rows.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_06481_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mm():
+    from paper_2505_06481_amd import mmoe
+    mmoe.lib()
+    assert torch.cuda.is_available()
+    return mmoe
+
+
+@pytest.fixture(scope="module")
+def gc():
+    import gpu_common
+    return gpu_common
+
+
+def staged_vs_oracle(mm, gc, oracle, cfg, inp=None):
+    """Run the four stages one by one through the C ABI and compare each with the oracle."""
+    print(f"case {cfg.name} T={cfg.T} d={cfg.d_model} f={cfg.d_ff} V={cfg.V} E={cfg.E} k={cfg.top_k} "
+          f"{cfg.dtype} {cfg.act} seed={cfg.seed}", flush=True)
+    case = gc.DeviceCase(cfg, inp)
+    inp, sh, dt = case.inp, case.shape, cfg.dtype
+    ref = oracle.layer_forward(inp, cfg.top_k, dt, cfg.act)
+
+    idx, w = mm.route(sh, case.X, case.vid, case.Wr, case.br)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), ref["topk_idx"]), "selected experts differ"
+    np.testing.assert_allclose(w.cpu().numpy(), ref["topk_w"], rtol=2e-6, atol=1e-7)
+
+    slot, counts, offsets, perm, inv, Xg = mm.remap_permute(sh, case.X, case.vid, idx, case.M, case.ws)
+    torch.cuda.synchronize()
+    for name, t in (("slot", slot), ("counts", counts), ("offsets", offsets), ("perm", perm), ("inv_perm", inv)):
+        assert np.array_equal(t.cpu().numpy(), ref[name]), name
+    assert np.array_equal(gc.bits(Xg), ref["Xg"]), "gathered rows differ"
+
+    Yg = mm.expert_ffn(sh, Xg, offsets, case.W1p, case.W3p, case.W2p, case.ws)
+    torch.cuda.synchronize()
+    gc.assert_close(gc.to_np64(Yg), ref["Yg"], dt, "Yg")
+
+    Y = mm.combine(sh, Yg, inv, w)
+    torch.cuda.synchronize()
+    gc.assert_close(gc.to_np64(Y), ref["Y"], dt, "Y (staged)")
+
+    Y2 = case.forward()
+    torch.cuda.synchronize()
+    assert torch.equal(Y2, Y), "fused entry point differs from the staged path"
+    Y3 = case.forward()
+    torch.cuda.synchronize()
+    assert torch.equal(Y3, Y2), "two runs differ: the path is not deterministic"
+    return case, ref
+
+
+SMALL = [
+    # weight-streaming kernels (few rows per slot), ragged row counts, several 16-row blocks
+    synth.Config("s_bf16_swiglu", 45, 512, 768, 3, 4, 2, "bf16", "swiglu", seed=1),
+    synth.Config("s_bf16_relu", 70, 256, 512, 2, 8, 1, "bf16", "relu", seed=2),
+    synth.Config("s_f32_relu", 33, 256, 512, 2, 4, 1, "f32", "relu", seed=3),
+    synth.Config("s_f32_swiglu", 50, 512, 256, 2, 4, 2, "f32", "swiglu", seed=4, bias_alpha=0.5),
+    synth.Config("s_f32_many_rows", 300, 256, 256, 1, 2, 1, "f32", "relu", seed=5),     # > 32 rows: passes
+    # matrix-core tiled kernels (many rows per slot), ragged tails, several tiles per slot
+    synth.Config("t_bf16_swiglu", 700, 512, 768, 2, 4, 2, "bf16", "swiglu", seed=6),
+    synth.Config("t_bf16_relu", 900, 256, 512, 3, 4, 1, "bf16", "relu", seed=7),
+    synth.Config("t_bf16_skew", 1500, 256, 256, 4, 8, 2, "bf16", "swiglu", seed=8, vid_mode="zipf",
+                 bias_alpha=1.0),
+    synth.Config("t_bf16_topk_all", 400, 256, 256, 1, 3, 3, "bf16", "swiglu", seed=9),   # top_k = E
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
+def test_small_cases_every_stage(mm, gc, oracle, cfg):
+    staged_vs_oracle(mm, gc, oracle, cfg)
+
+
+def test_edge_cases(mm, gc, oracle):
+    # a single token
+    staged_vs_oracle(mm, gc, oracle, synth.Config("one_token", 1, 256, 256, 2, 4, 2, "bf16", "swiglu", seed=10))
+    # every pick lands in one slot, all other slots are empty; two picks of a token share a slot
+    cfg = synth.Config("one_slot", 130, 256, 256, 2, 4, 2, "bf16", "swiglu", seed=11)
+    inp = synth.make_inputs(cfg)
+    inp["M"][:] = 2
+    case, ref = staged_vs_oracle(mm, gc, oracle, cfg, inp)
+    assert ref["counts"][2] == 260 and ref["counts"].sum() == 260
+    # exact ties in the router: duplicated router rows and an all-zero token
+    cfg = synth.Config("ties", 64, 256, 256, 1, 6, 3, "f32", "relu", seed=12)
+    inp = synth.make_inputs(cfg)
+    inp["Wr"][0, 4] = inp["Wr"][0, 1]
+    inp["Wr"][0, 5] = inp["Wr"][0, 2]
+    inp["X"][7] = 0.0
+    case, ref = staged_vs_oracle(mm, gc, oracle, cfg, inp)
+    assert list(ref["topk_idx"][7]) == [0, 1, 2]
+    # E above one wavefront's width, k = 8
+    staged_vs_oracle(mm, gc, oracle, synth.Config("wide_e", 40, 256, 256, 1, 130, 8, "bf16", "relu", seed=13))
+
+
+def test_validate_inputs(mm, gc):
+    cfg = synth.Config("val", 16, 256, 256, 2, 4, 1, "f32", "relu", seed=14)
+    case = gc.DeviceCase(cfg)
+    assert mm.validate_inputs(case.shape, case.vid, case.M, case.ws)
+    bad = case.vid.clone()
+    bad[3] = 2
+    assert not mm.validate_inputs(case.shape, bad, case.M, case.ws)
+    badM = case.M.clone()
+    badM[1, 1] = case.S
+    assert not mm.validate_inputs(case.shape, case.vid, badM, case.ws)
+
+
+def test_pack_round_trip(mm, gc):
+    cfg = synth.Config("pack", 4, 256, 512, 1, 3, 1, "bf16", "swiglu", seed=15)
+    inp = synth.make_inputs(cfg)
+    case = gc.DeviceCase(cfg, inp)
+    assert np.array_equal(gc.bits(case.W1p), inp["W1"].transpose(0, 2, 1))
+    assert np.array_equal(gc.bits(case.W3p), inp["W3"].transpose(0, 2, 1))
+    assert np.array_equal(gc.bits(case.W2p), inp["W2"].transpose(0, 2, 1))
+
+
+FULL_SMALL = ["switch8_fp32_v2_t128", "switch8_bf16_v4_t4096", "mixtral_decode_bf16_v2_t64"]
+
+
+@pytest.mark.parametrize("name", FULL_SMALL)
+def test_benchmark_shapes_full_parity(mm, gc, oracle, name):
+    staged_vs_oracle(mm, gc, oracle, synth.CONFIGS[name])
+
+
+@pytest.mark.parametrize("name", ["mixtral_prefill_bf16_v2_t8192", "mixtral_skew_bf16_v4_t16384"])
+def test_benchmark_shapes_sampled_parity(mm, gc, oracle, name):
+    """Full-size layers in the benchmark's launch configuration: integer outputs on every
+    token, outputs on a seeded sample of rows (including rows of the smallest and the
+    largest slot) that the oracle evaluates one by one."""
+    cfg = synth.CONFIGS[name]
+    print(f"case {name}: generating", flush=True)
+    case = gc.DeviceCase(cfg)
+    inp, sh = case.inp, case.shape
+    print("routing oracle", flush=True)
+    idx_ref, w_ref, _ = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], cfg.top_k, cfg.dtype)
+    slot_ref, counts_ref, offsets_ref, perm_ref, inv_ref = oracle.remap_group(inp["vid"], idx_ref, inp["M"], case.S)
+
+    idx, w = mm.route(sh, case.X, case.vid, case.Wr, case.br)
+    slot, counts, offsets, perm, inv, Xg = mm.remap_permute(sh, case.X, case.vid, idx, case.M, case.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    np.testing.assert_allclose(w.cpu().numpy(), w_ref, rtol=2e-6, atol=1e-7)
+    for got, ref in ((slot, slot_ref), (counts, counts_ref), (offsets, offsets_ref), (perm, perm_ref), (inv, inv_ref)):
+        assert np.array_equal(got.cpu().numpy(), ref)
+    assert np.array_equal(gc.bits(Xg), inp["X"][perm_ref // cfg.top_k])
+    print("slot counts min/median/max:", counts_ref.min(), int(np.median(counts_ref)), counts_ref.max(), flush=True)
+
+    Y = case.forward()
+    torch.cuda.synchronize()
+    assert torch.isfinite(Y.float()).all()
+    rng = np.random.default_rng(7)
+    smallest, largest = int(np.argmin(np.where(counts_ref > 0, counts_ref, 1 << 30))), int(np.argmax(counts_ref))
+    toks = set(rng.choice(cfg.T, 20, replace=False).tolist())
+    for s in (smallest, largest):
+        rows = perm_ref[offsets_ref[s]:offsets_ref[s + 1]]
+        toks.update((rows[[0, len(rows) // 2, -1]] // cfg.top_k).tolist())   # first, middle, last row of the slot
+    toks = sorted(toks)
+    print(f"expert oracle on {len(toks)} sampled tokens", flush=True)
+    Y_ref = oracle.layer_tokens(inp, cfg.top_k, cfg.dtype, cfg.act, toks, routed=(idx_ref, w_ref, slot_ref))
+    gc.assert_close(gc.to_np64(Y[toks]), Y_ref, cfg.dtype, "Y (sampled)")

@@ -1,0 +1,83 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, sizes the workspace, and turns bad arguments into error codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_06481_amd import build as mbuild
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def mm():
+    if mbuild.is_stale():
+        mbuild.build()
+    from paper_2505_06481_amd import mmoe
+    mmoe.lib()
+    return mmoe
+
+
+def test_every_declared_symbol_is_exported(mm):
+    header = open(os.path.join(ROOT, "include", "mmoe.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(mmoe_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(mm.EXPORTS)
+    L = ctypes.CDLL(os.path.join(ROOT, "paper_2505_06481_amd", "libmmoe.so"))
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_workspace_size_accounts_for_every_intermediate(mm):
+    sh = mm.make_shape(8192, 4096, 14336, 2, 8, 12, 2, "bf16", "swiglu")
+    P = 8192 * 2
+    need = P * 4096 * 2 + P * 14336 * 2 + P * 4096 * 4     # Xg + H + Yg
+    got = mm.workspace_bytes(sh)
+    assert need <= got <= need + (1 << 20)
+    assert mm.workspace_bytes(mm.make_shape(8, 100, 256, 1, 1, 1, 1, "f32", "relu")) == 0
+
+
+def test_bad_arguments_become_error_codes(mm):
+    L = mm.lib()
+    ok = mm.make_shape(4, 256, 256, 1, 2, 2, 1, "f32", "relu")
+    p = ctypes.c_void_p(4096)          # never dereferenced: checks fail before any launch
+    none = None
+
+    def route(shape, X=p, vid=p, Wr=p):
+        return L.mmoe_route(ctypes.byref(shape), X, vid, Wr, none, p, p, none)
+
+    assert route(ok, X=none) == -1                                                       # NULL
+    assert route(mm.make_shape(0, 256, 256, 1, 2, 2, 1, "f32", "relu")) == -2            # dimension
+    assert route(mm.make_shape(4, 256, 256, 1, 2, 2, 3, "f32", "relu")) == -3            # top_k > E
+    assert route(mm.make_shape(4, 256, 256, 1, 16, 2, 9, "f32", "relu")) == -3           # top_k > 8
+    assert route(mm.make_shape(4, 256, 256, 1, 2, 2, 1, 7, "relu")) == -4                # dtype
+    assert route(mm.make_shape(4, 256, 256, 1, 2, 2, 1, "f32", 5)) == -4                 # activation
+    assert route(mm.make_shape(4, 200, 256, 1, 2, 2, 1, "f32", "relu")) == -8            # multiple of 256
+    assert route(mm.make_shape(4, 256, 256, 1, 300, 2, 1, "f32", "relu")) == -9          # E limit
+    assert route(mm.make_shape(4, 256, 256, 1, 2, 5000, 1, "f32", "relu")) == -9         # S limit
+    assert route(ok, X=ctypes.c_void_p(4100)) == -7                                      # alignment
+    # expert stage: W3 must match the activation; workspace must be large enough
+    gated = mm.make_shape(4, 256, 256, 1, 2, 2, 1, "bf16", "swiglu")
+    assert L.mmoe_expert_ffn(ctypes.byref(gated), p, p, p, none, p, p, p, 1 << 30, none) == -5
+    assert L.mmoe_expert_ffn(ctypes.byref(ok), p, p, p, p, p, p, p, 1 << 30, none) == -5
+    assert L.mmoe_expert_ffn(ctypes.byref(ok), p, p, p, none, p, p, p, 16, none) == -6
+    assert L.mmoe_expert_ffn(ctypes.byref(ok), p, p, p, none, p, p, none, 1 << 30, none) == -6
+    assert L.mmoe_layer_forward(ctypes.byref(ok), p, p, p, none, p, p, none, p, p, ctypes.c_void_p(4352), 8,
+                                none) == -6
+    assert L.mmoe_layer_forward(ctypes.byref(ok), p, p, p, none, p, p, none, p, p, ctypes.c_void_p(4100),
+                                1 << 30, none) == -7
+    assert L.mmoe_pack_weights(ctypes.byref(gated), p, none, p, p, p, p, none) == -5
+    assert L.mmoe_combine(ctypes.byref(ok), none, p, p, p, none) == -1
+    assert L.mmoe_remap_permute(ctypes.byref(ok), p, p, p, p, p, p, p, p, p, p, none, 0, none) == -6
+    for code in range(0, -11, -1):
+        assert mm.strerror(code) != "unknown status"
+    assert mm.strerror(-99) == "unknown status"
+
+
+def test_binding_refuses_host_tensors(mm):
+    import torch
+    sh = mm.make_shape(4, 256, 256, 1, 2, 2, 1, "f32", "relu")
+    with pytest.raises(ValueError):
+        mm.route(sh, torch.zeros(4, 256), torch.zeros(4, dtype=torch.int32), torch.zeros(1, 2, 256))
