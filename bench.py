@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the multi-model MoE layer forward on one MI355X.
+
+One step = one pass of the whole layer (route -> map/group -> expert FFN -> combine,
+``mmoe_layer_forward``) over one batch of seeded synthetic input that is already resident
+in HBM.  The default workload is the Mixtral-8x7B-shaped prefill layer (8192 tokens,
+2 variants); the Mixtral-shaped decode layer (64 tokens) is run right after it on the same
+pool and reported in the same JSON line under "decode".
+
+Prints ONE JSON line: tokens/s of the layer, the roofline fraction of its dominant kernel
+(timed live with HIP events recorded between the kernels of every timed step), and the CPU
+oracle timed on a bounded sample of the same workload as a reported baseline.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mixtral_prefill_bf16_v2_t8192")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-shaped companion run")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = 96 tokens per oracle thread")
+    return ap.parse_args()
+
+
+class HipEvents:
+    """hipEvent_t handles created straight from the HIP runtime (timing enabled)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.ev = (ctypes.c_void_p * n)()
+        for i in range(n):
+            h = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(h))
+            assert rc == 0, f"hipEventCreate failed ({rc})"
+            self.ev[i] = h
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.ev[a], self.ev[b])
+        assert rc == 0, f"hipEventElapsedTime failed ({rc})"
+        return float(ms.value)
+
+    def destroy(self):
+        for h in self.ev:
+            self.hip.hipEventDestroy(h)
+
+
+def run_workload(cfg, inp, pool, steps, warmup):
+    """Upload (pool already packed on the device), warm up, time `steps` layer passes."""
+    import numpy as np
+    import torch
+
+    from paper_2505_06481_amd import mmoe
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import gpu_common as gc
+
+    S = int(inp["S"])
+    shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act)
+    X, Wr = gc.to_dev(inp["X"], cfg.dtype), gc.to_dev(inp["Wr"], cfg.dtype)
+    vid, M = torch.from_numpy(inp["vid"]).cuda(), torch.from_numpy(inp["M"]).cuda()
+    br = None if inp["br"] is None else torch.from_numpy(inp["br"]).cuda()
+    ws = mmoe.alloc_workspace(shape)
+    Y = torch.empty((cfg.T, cfg.d_model), dtype=X.dtype, device="cuda")
+    W1p, W3p, W2p = pool
+    NE = mmoe.NUM_EVENTS
+    events = HipEvents(NE * steps)
+
+    def step(i=None):
+        ev = None
+        if i is not None:
+            ev = ctypes.cast(ctypes.byref(events.ev, i * NE * ctypes.sizeof(ctypes.c_void_p)),
+                             ctypes.POINTER(ctypes.c_void_p))
+        mmoe.layer_forward(shape, X, vid, Wr, br, M, W1p, W3p, W2p, ws, Y=Y, events=ev)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    stage_ms = np.zeros((steps, NE - 1))
+    for i in range(steps):
+        for s in range(NE - 1):
+            stage_ms[i, s] = events.elapsed_ms(i * NE + s, i * NE + s + 1)
+    events.destroy()
+    names = ["route", "permute", "ffn_up", "ffn_down", "combine"]
+    stages = {n: float(stage_ms[:, j].mean()) for j, n in enumerate(names)}
+
+    # per-slot row counts of this batch (for the byte/flop accounting of the roofline)
+    sl = mmoe.remap_permute(shape, X, vid, mmoe.route(shape, X, vid, Wr, br)[0], M, ws)
+    counts = sl[1].cpu().numpy()
+    torch.cuda.synchronize()
+    return dict(ms_per_step=wall / steps * 1e3, stages_ms=stages, counts=counts, S=S, Y=Y)
+
+
+def roofline(cfg, res, skinny):
+    """Roofline of the dominant kernel, the experts' up product (W1 and, when gated, W3)."""
+    d, f, k = cfg.d_model, cfg.d_ff, cfg.top_k
+    nw = 2 if cfg.act == "swiglu" else 1
+    es = 2 if cfg.dtype == "bf16" else 4
+    P = cfg.T * k
+    dur_s = res["stages_ms"]["ffn_up"] * 1e-3
+    if skinny:
+        # weight streaming: every slot with at least one row reads its nw [f, d] matrices once
+        active = int((res["counts"] > 0).sum())
+        alg_bytes = active * nw * d * f * es + P * d * es + P * f * es
+        ach = alg_bytes / dur_s / 1e9
+        return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
+                    traffic=None, kernel="skinny_kernel (up product)", bytes_per_launch=alg_bytes,
+                    avg_launch_ms=dur_s * 1e3)
+    flops = 2.0 * P * d * f * nw
+    ach = flops / dur_s / 1e12
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_MFMA_TFLOPS
+    return dict(bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak, traffic=None,
+                kernel="tiled_kernel (up product)", flops_per_launch=flops, avg_launch_ms=dur_s * 1e3)
+
+
+def cpu_baseline(cfg, inp, n_tokens):
+    """The oracle as it stands, timed on this host: routing and grouping over every token,
+    the expert stage and the combination over a seeded sample of tokens, extrapolated
+    linearly to the whole batch."""
+    import numpy as np
+
+    import oracle
+
+    threads = oracle.threads()
+    n = n_tokens if n_tokens > 0 else 96 * threads
+    n = min(n, cfg.T)
+    t0 = time.perf_counter()
+    idx, w, _ = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], cfg.top_k, cfg.dtype)
+    slot, *_ = oracle.remap_group(inp["vid"], idx, inp["M"], int(inp["S"]))
+    t_route = time.perf_counter() - t0
+    toks = np.sort(np.random.default_rng(0).choice(cfg.T, n, replace=False))
+    t0 = time.perf_counter()
+    oracle.layer_tokens(inp, cfg.top_k, cfg.dtype, cfg.act, toks, routed=(idx, w, slot))
+    t_ffn = time.perf_counter() - t0
+    est = t_route + t_ffn * cfg.T / n
+    return dict(value=cfg.T / est, unit="tokens/s", cores=threads, kind="oracle",
+                sample=f"routing+grouping on all {cfg.T} tokens ({t_route:.2f} s); expert FFN+combine on {n} "
+                       f"seeded tokens ({t_ffn:.2f} s), extrapolated linearly to {cfg.T}")
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this layer runs on one GPU; --gpus must be 1 (no sharding, no collectives)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2505_06481_amd import mmoe, synth
+
+    mmoe.lib()  # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import gpu_common as gc
+
+    cfg = synth.CONFIGS[a.workload]
+    inp = synth.make_inputs(cfg)
+    S = int(inp["S"])
+    shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act)
+    W1, W3, W2 = (gc.to_dev(inp[k], cfg.dtype) for k in ("W1", "W3", "W2"))
+    pool = mmoe.pack_weights(shape, W1, W3, W2)   # one-time repacking at pool load, untimed
+    torch.cuda.synchronize()
+    del W1, W3, W2
+    torch.cuda.empty_cache()
+
+    skinny = cfg.dtype == "f32" or cfg.T * cfg.top_k <= 48 * S
+    res = run_workload(cfg, inp, pool, a.steps, a.warmup)
+    ms = res["ms_per_step"]
+    nw = 3 if cfg.act == "swiglu" else 2
+    layer_flops = 2.0 * cfg.T * cfg.top_k * cfg.d_model * cfg.d_ff * nw
+    out = {
+        "metric": "MoE-layer tokens/s (multi-model consolidated pool, layer forward)",
+        "value": cfg.T / (ms * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "T": cfg.T, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "V": cfg.V,
+                   "E": cfg.E, "top_k": cfg.top_k, "S": S, "act": cfg.act, "seed": cfg.seed,
+                   "slot_rows_min_med_max": [int(res["counts"].min()), int(sorted(res["counts"])[S // 2]),
+                                             int(res["counts"].max())]},
+        "layer_tflops": layer_flops / (ms * 1e-3) / 1e12,
+        "stages_ms": res["stages_ms"],
+        "roofline": roofline(cfg, res, skinny),
+    }
+
+    if not a.no_decode and cfg.name == "mixtral_prefill_bf16_v2_t8192":
+        dcfg = synth.CONFIGS["mixtral_decode_bf16_v2_t64"]
+        dinp = synth.make_inputs(dcfg, weights=False)   # same seed, same pool: only the batch differs
+        assert int(dinp["S"]) == S and (dinp["M"] == inp["M"]).all()
+        dres = run_workload(dcfg, dinp, pool, max(a.steps, 50), a.warmup)
+        dms = dres["ms_per_step"]
+        active = int((dres["counts"] > 0).sum())
+        out["decode"] = {
+            "config": {"workload": dcfg.name, "T": dcfg.T, "S": S, "active_slots": active},
+            "value": dcfg.T / (dms * 1e-3), "unit": "tokens/s", "ms_per_step": dms,
+            "layer_gbs": active * 3 * dcfg.d_model * dcfg.d_ff * 2 / (dms * 1e-3) / 1e9,
+            "stages_ms": dres["stages_ms"],
+            "roofline": roofline(dcfg, dres, True),
+        }
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, a.cpu_sample_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

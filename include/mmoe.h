@@ -163,6 +163,29 @@ int mmoe_layer_forward(const mmoe_shape *shape, const void *X, const int32_t *vi
                        const void *W2p, void *Y, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * mmoe_layer_forward with timing marks, for benchmarks and profilers.  `events` is a HOST
+ * array of MMOE_NUM_EVENTS hipEvent_t (as void*), created by the caller with timing
+ * enabled; events[MMOE_EV_START] is recorded on `stream` before the first kernel and
+ * events[i] right after the last kernel of stage i, so that the elapsed time between two
+ * consecutive events is the duration of one stage (the expert stage is split into its up
+ * product + activation and its down product: one kernel each).  NULL `events` makes this
+ * identical to mmoe_layer_forward.  The results do not depend on `events`.
+ */
+enum {
+    MMOE_EV_START = 0,
+    MMOE_EV_ROUTE = 1,    /* after step R                                         */
+    MMOE_EV_PERMUTE = 2,  /* after steps M and G                                  */
+    MMOE_EV_FFN_UP = 3,   /* after H = act(Xg W1 [, Xg W3])                       */
+    MMOE_EV_FFN_DOWN = 4, /* after Yg = H W2                                      */
+    MMOE_EV_COMBINE = 5,  /* after step C                                         */
+    MMOE_NUM_EVENTS = 6
+};
+int mmoe_layer_forward_events(const mmoe_shape *shape, const void *X, const int32_t *vid,
+                              const void *Wr, const float *br, const int32_t *M, const void *W1p,
+                              const void *W3p, const void *W2p, void *Y, void *ws, size_t ws_bytes,
+                              void *stream, void *const *events);
+
+/*
  * Debugging aid, SYNCHRONISES the stream: checks on the device that every vid[t] is in
  * [0,V) and every M[v][e] in [0,S).  Returns 0 if so, 1 if not, a negative status on
  * argument errors.  `ws` needs 256 bytes.

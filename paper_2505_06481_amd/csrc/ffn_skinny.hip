@@ -180,7 +180,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
 
 template <typename T>
 static int run_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st)
+                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
 {
     const int d = s.d_model, f = s.d_ff;
     dim3 block(kSkThreads);
@@ -192,16 +192,17 @@ static int run_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offset
     else
         hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH>), g1, block, 0, st, (const T*)Xg, offsets,
                            (const T*)W1p, nul, H, d, f);
+    if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
     hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModePlainF32>), g2, block, 0, st, (const T*)H, offsets,
                        (const T*)W2p, nul, (void*)Yg, f, d);
     return launch_status();
 }
 
 int launch_ffn_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st)
+                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
 {
-    if (s.dtype == MMOE_BF16) return run_skinny<uint16_t>(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st);
-    return run_skinny<float>(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st);
+    if (s.dtype == MMOE_BF16) return run_skinny<uint16_t>(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st, mid);
+    return run_skinny<float>(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st, mid);
 }
 
 }  // namespace mmoe

@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kTThreads) void tiled_kernel(const uint16_t* __rest
 }
 
 int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                     const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st)
+                     const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
 {
     if (s.dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     const int P = s.T * s.top_k, d = s.d_model, f = s.d_ff;
@@ -197,6 +197,7 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets
     else
         hipLaunchKernelGGL(tiled_kernel<kTModeReluH>, dim3(mtiles, f / kBN), block, 0, st, (const uint16_t*)Xg,
                            offsets, (const uint16_t*)W1p, nul, H, d, f, s.S);
+    if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
     hipLaunchKernelGGL(tiled_kernel<kTModePlainF32>, dim3(mtiles, d / kBN), block, 0, st, (const uint16_t*)H,
                        offsets, (const uint16_t*)W2p, nul, (void*)Yg, f, d, s.S);
     return launch_status();

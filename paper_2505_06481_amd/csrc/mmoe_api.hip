@@ -159,9 +159,10 @@ int mmoe_combine(const mmoe_shape* shape, const float* Yg, const int32_t* inv_pe
     return launch_combine(*shape, Yg, inv_perm, topk_w, Y, (hipStream_t)stream);
 }
 
-int mmoe_layer_forward(const mmoe_shape* shape, const void* X, const int32_t* vid, const void* Wr,
-                       const float* br, const int32_t* M, const void* W1p, const void* W3p, const void* W2p,
-                       void* Y, void* ws, size_t ws_bytes, void* stream)
+int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int32_t* vid, const void* Wr,
+                              const float* br, const int32_t* M, const void* W1p, const void* W3p,
+                              const void* W2p, void* Y, void* ws, size_t ws_bytes, void* stream,
+                              void* const* events)
 {
     int rc = check_shape(shape);
     if (rc) return rc;
@@ -174,25 +175,41 @@ int mmoe_layer_forward(const mmoe_shape* shape, const void* X, const int32_t* vi
         misaligned(br, 4) || misaligned(M, 4))
         return MMOE_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
+    auto mark = [&](int i) -> int {
+        if (!events) return MMOE_OK;
+        return hipEventRecord((hipEvent_t)events[i], st) == hipSuccess ? MMOE_OK : MMOE_ERR_LAUNCH;
+    };
     char* w = (char*)ws;
     int32_t* topk_idx = (int32_t*)(w + L.topk_idx);
     float* topk_w = (float*)(w + L.topk_w);
     int32_t* offsets = (int32_t*)(w + L.offsets);
     int32_t* inv_perm = (int32_t*)(w + L.inv_perm);
     float* Yg = (float*)(w + L.Yg);
+    hipEvent_t mid = events ? (hipEvent_t)events[MMOE_EV_FFN_UP] : nullptr;
 
-    rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st);
-    if (rc) return rc;
+    if ((rc = mark(MMOE_EV_START))) return rc;
+    if ((rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st))) return rc;
+    if ((rc = mark(MMOE_EV_ROUTE))) return rc;
     rc = launch_permute(*shape, X, vid, topk_idx, M, (int32_t*)(w + L.slot), (int32_t*)(w + L.counts), offsets,
                         (int32_t*)(w + L.perm), inv_perm, w + L.Xg, (int32_t*)(w + L.blk_counts),
                         (int32_t*)(w + L.blk_base), L.nblk, st);
     if (rc) return rc;
+    if ((rc = mark(MMOE_EV_PERMUTE))) return rc;
     if (use_skinny(*shape))
-        rc = launch_ffn_skinny(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, st);
+        rc = launch_ffn_skinny(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, st, mid);
     else
-        rc = launch_ffn_tiled(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, st);
+        rc = launch_ffn_tiled(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, st, mid);
     if (rc) return rc;
-    return launch_combine(*shape, Yg, inv_perm, topk_w, Y, st);
+    if ((rc = mark(MMOE_EV_FFN_DOWN))) return rc;
+    if ((rc = launch_combine(*shape, Yg, inv_perm, topk_w, Y, st))) return rc;
+    return mark(MMOE_EV_COMBINE);
+}
+
+int mmoe_layer_forward(const mmoe_shape* shape, const void* X, const int32_t* vid, const void* Wr,
+                       const float* br, const int32_t* M, const void* W1p, const void* W3p, const void* W2p,
+                       void* Y, void* ws, size_t ws_bytes, void* stream)
+{
+    return mmoe_layer_forward_events(shape, X, vid, Wr, br, M, W1p, W3p, W2p, Y, ws, ws_bytes, stream, nullptr);
 }
 
 int mmoe_validate_inputs(const mmoe_shape* shape, const int32_t* vid, const int32_t* M, void* ws,

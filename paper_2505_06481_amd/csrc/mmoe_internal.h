@@ -54,10 +54,14 @@ int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const
                    const int32_t* M, int32_t* slot, int32_t* counts, int32_t* offsets, int32_t* perm,
                    int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk,
                    hipStream_t st);
+// Expert stage.  `mid`, when not null, is recorded between the up product (+ activation)
+// and the down product.
 int launch_ffn_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st);
+                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
+                      hipEvent_t mid = nullptr);
 int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                     const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st);
+                     const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
+                     hipEvent_t mid = nullptr);
 int launch_combine(const mmoe_shape& s, const float* Yg, const int32_t* inv_perm, const float* topk_w,
                    void* Y, hipStream_t st);
 int launch_pack(const mmoe_shape& s, const void* W1, const void* W3, const void* W2, void* W1p, void* W3p,

@@ -25,7 +25,8 @@ _TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
 
 EXPORTS = [
     "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
-    "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_validate_inputs",
+    "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_layer_forward_events",
+    "mmoe_validate_inputs",
 ]
 
 
@@ -70,6 +71,7 @@ def lib():
         L.mmoe_expert_ffn.argtypes = [sp] + [vp] * 7 + [sz, vp]
         L.mmoe_combine.argtypes = [sp] + [vp] * 5
         L.mmoe_layer_forward.argtypes = [sp] + [vp] * 10 + [sz, vp]
+        L.mmoe_layer_forward_events.argtypes = [sp] + [vp] * 10 + [sz, vp, vp]
         L.mmoe_validate_inputs.argtypes = [sp, vp, vp, vp, sz, vp]
         for n in EXPORTS[2:]:
             getattr(L, n).restype = i
@@ -180,18 +182,23 @@ def combine(shape: Shape, Yg, inv_perm, topk_w):
     return Y
 
 
-def layer_forward(shape: Shape, X, vid, Wr, br, M, W1p, W3p, W2p, ws, Y=None):
+NUM_EVENTS = 6
+EV_START, EV_ROUTE, EV_PERMUTE, EV_FFN_UP, EV_FFN_DOWN, EV_COMBINE = range(NUM_EVENTS)
+
+
+def layer_forward(shape: Shape, X, vid, Wr, br, M, W1p, W3p, W2p, ws, Y=None, events=None):
+    """``events``: optional ctypes array of NUM_EVENTS hipEvent_t handles (c_void_p)."""
     dt = _TORCH_DT[shape.dtype]
     S, d, f = shape.S, shape.d_model, shape.d_ff
     if Y is None:
         Y = torch.empty((shape.T, d), dtype=dt, device=X.device)
-    rc = lib().mmoe_layer_forward(ctypes.byref(shape), _ptr(X, dt, shape.T * d, "X"),
+    rc = lib().mmoe_layer_forward_events(ctypes.byref(shape), _ptr(X, dt, shape.T * d, "X"),
                                   _ptr(vid, torch.int32, shape.T, "vid"), _ptr(Wr, dt, shape.V * shape.E * d, "Wr"),
                                   _ptr(br, torch.float32, shape.V * shape.E, "br"),
                                   _ptr(M, torch.int32, shape.V * shape.E, "M"), _ptr(W1p, dt, S * d * f, "W1p"),
                                   _ptr(W3p, dt, S * d * f, "W3p"), _ptr(W2p, dt, S * d * f, "W2p"),
                                   _ptr(Y, dt, shape.T * d, "Y"), _ptr(ws, torch.uint8, None, "ws"), ws.numel(),
-                                  _stream())
+                                  _stream(), events)
     _check(rc, "mmoe_layer_forward")
     return Y
 
