@@ -3,151 +3,259 @@
 // where the layer's time goes (section 5.1).
 //
 // Both products are  out[r, n] = sum_k A[r, k] * W[s][n][k]  over the packed pool, bf16
-// inputs, fp32 accumulation on v_mfma_f32_32x32x16_bf16.  A workgroup computes a
-// 128-row x 128-feature tile of one slot; the ragged row ranges come from the device
-// array `offsets`, so the tile -> (slot, first row) map is resolved on the device and the
-// host never waits for the histogram.
+// inputs, fp32 accumulation on v_mfma_f32_32x32x16_bf16.
 //
-// Matrix-core operand roles: weights are the 32-row operand, tokens the 32-column one.
-// A lane then owns, for one token, groups of 4 consecutive output features, which makes
-// the gate/up pairing of SwiGLU lane-local and the stores 8 or 16 bytes wide.  For the
-// gated product a workgroup's 128 weight rows are 64 rows of W1 and the same 64 rows of
-// W3, interleaved per wavefront so that each lane holds matching gate and up values.
+// Tile: 256 token rows x 256 weight rows x 64 k per step, one workgroup of four
+// wavefronts per compute unit.  Each wavefront owns all 256 token rows and 64 weight rows
+// (for the gated product: 32 rows of W1 and the same 32 rows of W3, so that SiLU(gate)*up
+// is lane-local): 8 x 2 accumulator tiles of 32x32, 256 accumulator registers.  Weights are
+// the 32-row matrix-core operand and tokens the 32-column one, hence a lane owns, for one
+// token, groups of 4 consecutive output features and stores 8 or 16 bytes at a time.
 //
-// LDS tiles are [row][64 k] bf16 (128 bytes a row), 16-byte pieces xor-swizzled with
-// (row >> 1) & 7 so that both the staging writes and the operand reads are conflict-free.
+// Memory pipeline: global -> LDS copies are issued by the DMA path (global_load_lds, 16
+// bytes per lane, no staging registers) into a double-buffered pair of LDS tiles; the
+// copies of step kt+1 are in flight while step kt is multiplied; one barrier per step.
+// LDS tiles are [row][64 k] bf16 (128 bytes a row) with the 16-byte pieces xor-swizzled by
+// (row >> 1) & 7: the DMA writes a wavefront's 64 pieces to consecutive LDS addresses, so
+// the swizzle is applied on the global side (which piece a lane fetches).
+//
+// Ragged groups: row ranges come from the device array `offsets`.  A one-workgroup
+// preparation kernel turns them into a table of row tiles; the product kernels map their
+// workgroup id to (slot, row tile, feature tile) through that table, so the host never
+// waits for the histogram.  Workgroup ids are dealt round-robin to the 8 XCDs by the
+// hardware; the id -> tile map gives each XCD a contiguous run of tiles ordered
+// (slot, feature tile, row tile), so the workgroups resident on one XCD share weight and
+// activation panels in that XCD's L2.
 #include "mmoe_internal.h"
 
 namespace mmoe {
 
 enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2 };
 
-constexpr int kBM = 128;  // token rows per tile
-constexpr int kBN = 128;  // weight rows per tile
+constexpr int kBM = 256;  // token rows per tile
+constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
 constexpr int kTThreads = 256;
+constexpr int kXcds = 8;
+constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB
 
-__device__ __forceinline__ int swz(int row, int piece) { return row * 128 + ((piece ^ ((row >> 1) & 7)) << 4); }
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
 __device__ __forceinline__ float silu_mul_t(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
 
-template <int MODE>
-__global__ __launch_bounds__(kTThreads) void tiled_kernel(const uint16_t* __restrict__ A,
-                                                          const int32_t* __restrict__ offsets,
-                                                          const uint16_t* __restrict__ W0,
-                                                          const uint16_t* __restrict__ W1, void* __restrict__ out,
-                                                          int K, int N, int S)
+// Table written by tile_table_kernel: tab[0] = number of row tiles; tab[1 + s] = first row
+// tile of slot s (tab[1 + S] = number of row tiles again).
+__global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restrict__ offsets,
+                                                         int32_t* __restrict__ tab, int S)
 {
-    __shared__ __attribute__((aligned(16))) char lds_a[kBM * kBK * 2];
-    __shared__ __attribute__((aligned(16))) char lds_b[kBN * kBK * 2];
-    __shared__ int sh_slot, sh_m0;
-
-    // which slot and which rows does m-tile blockIdx.x cover?
+    __shared__ int part[256];
+    // thread t covers slots [t*per, (t+1)*per)
+    const int per = (S + 255) / 256;
+    const int s_lo = min((int)threadIdx.x * per, S), s_hi = min(s_lo + per, S);
+    int sum = 0;
+    for (int s = s_lo; s < s_hi; ++s) sum += (offsets[s + 1] - offsets[s] + kBM - 1) / kBM;
+    part[threadIdx.x] = sum;
+    __syncthreads();
     if (threadIdx.x == 0) {
-        int mt = blockIdx.x, found = -1, m0 = 0, seen = 0;
-        for (int s = 0; s < S; ++s) {
-            int c = offsets[s + 1] - offsets[s];
-            int nt = (c + kBM - 1) / kBM;
-            if (mt < seen + nt) {
-                found = s;
-                m0 = (mt - seen) * kBM;
-                break;
-            }
-            seen += nt;
+        int run = 0;
+        for (int t = 0; t < 256; ++t) {
+            int c = part[t];
+            part[t] = run;
+            run += c;
         }
-        sh_slot = found;
-        sh_m0 = m0;
+        tab[0] = run;
+        tab[1 + S] = run;
     }
     __syncthreads();
-    const int s = sh_slot;
-    if (s < 0) return;
-    const int m0 = sh_m0;
+    int run = part[threadIdx.x];
+    for (int s = s_lo; s < s_hi; ++s) {
+        tab[1 + s] = run;
+        run += (offsets[s + 1] - offsets[s] + kBM - 1) / kBM;
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __restrict__ A,
+                                                             const int32_t* __restrict__ offsets,
+                                                             const int32_t* __restrict__ tab,
+                                                             const uint16_t* __restrict__ W0,
+                                                             const uint16_t* __restrict__ W1,
+                                                             void* __restrict__ out, int K, int N, int S, int NT)
+{
+    __shared__ __attribute__((aligned(1024))) char lds_a0[kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char lds_b0[kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char lds_a1[kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char lds_b1[kTileBytes];
+
+    // ---- workgroup id -> tile ------------------------------------------------------------
+    const int total = tab[0] * NT;
+    const int chunk = (total + kXcds - 1) / kXcds;
+    const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+    const int L = xcd * chunk + local;
+    if (local >= chunk || L >= total) return;  // uniform over the workgroup
+    // slot s with tab[1+s]*NT <= L < tab[2+s]*NT (binary search; empty slots have equal bounds)
+    int lo = 0, hi = S;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (tab[1 + mid] * NT <= L) lo = mid; else hi = mid;
+    }
+    const int s = lo;
+    const int mt_s = tab[2 + s] - tab[1 + s];   // row tiles of this slot (> 0 by construction)
+    const int rem = L - tab[1 + s] * NT;
+    const int nt = rem / mt_s, mi = rem % mt_s;  // row tile fastest
+    const int m0 = mi * kBM;
     const int r0 = offsets[s];
     const int cnt = offsets[s + 1] - r0;
 
     constexpr int kFeat = MODE == kTModeSwigluH ? kBN / 2 : kBN;  // output features per tile
-    const int n0 = blockIdx.y * kFeat;
+    const int n0 = nt * kFeat;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;  // wavefront grid: 2 (tokens) x 2 (weight rows)
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps LDS bases in scalar registers
 
-    // staging: thread copies pieces id = i*256 + tid, i < 4; row = id / 8, piece = id % 8
-    const uint16_t* ga[4];
-    const uint16_t* gb[4];
-    int la[4];
+    // ---- DMA addressing --------------------------------------------------------------------
+    // Instruction i of wavefront w fills LDS rows g*8 .. g*8+7, g = w*8 + i, of a tile: lane
+    // -> (row r = lane/8 inside the group, physical piece lane%8).  The piece fetched is the
+    // logical one that the swizzle stores there.  Addresses are a uniform 64-bit base (scalar
+    // registers, advanced by 128 bytes per k step) plus a per-lane 32-bit byte offset that
+    // never changes.
+    const char* a_base = reinterpret_cast<const char*>(A) + (size_t)r0 * K * 2;
+    const char* b_base0 = reinterpret_cast<const char*>(W0) + (size_t)s * N * K * 2;
+    const char* b_base1 = MODE == kTModeSwigluH ? reinterpret_cast<const char*>(W1) + (size_t)s * N * K * 2 : b_base0;
+    uint32_t a_off[8], b_off[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int id = i * kTThreads + tid, row = id >> 3, pc = id & 7;
-        int ar = min(m0 + row, cnt - 1);  // rows past the end re-read the last row; never stored
-        ga[i] = A + (size_t)(r0 + ar) * K + pc * 8;
-        // weight row of LDS row `row`: gated tiles interleave 32 rows of W1 with 32 rows of W3
-        const uint16_t* wb;
+    for (int i = 0; i < 8; ++i) {
+        const int row = (wave * 8 + i) * 8 + (lane >> 3);
+        const int piece = (lane & 7) ^ ((row >> 1) & 7);
+        const int ar = min(m0 + row, cnt - 1);  // rows past the end re-read the last row; never stored
+        a_off[i] = (uint32_t)ar * (uint32_t)K * 2u + piece * 16;
         int feat;
-        if (MODE == kTModeSwigluH) {
-            int blk = row >> 5;              // 0..3: wavefront column wn = blk/2, gate/up = blk%2
-            feat = (blk >> 1) * 32 + (row & 31);
-            wb = (blk & 1) ? W1 : W0;
-        } else {
-            feat = row;
-            wb = W0;
-        }
-        gb[i] = wb + ((size_t)s * N + n0 + feat) * K + pc * 8;
-        la[i] = swz(row, pc);
+        if (MODE == kTModeSwigluH) feat = (wave * 8 + i) / 8 * 32 + (row & 31);  // row>>5 = wave*2 + i/4; /2 = wave
+        else feat = row;
+        b_off[i] = (uint32_t)(n0 + feat) * (uint32_t)K * 2u + piece * 16;
     }
+    const int dma_off = wave * 8 * 1024;  // this wavefront's first row group, in bytes
 
-    f32x16 acc[2][2];  // [weight-row tile][token tile]
+    // i < 4 of a gated tile are rows of W1 (gate), i >= 4 rows of W3 (up): row>>5 = 2*wave + i/4.
+    auto issue = [&](char* la, char* lb, int kt) {
+        const char* ab = a_base + (size_t)kt * (kBK * 2);
+        const char* bb0 = b_base0 + (size_t)kt * (kBK * 2);
+        const char* bb1 = b_base1 + (size_t)kt * (kBK * 2);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(ab + a_off[i]), (lptr_t)(la + dma_off + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)((i < 4 ? bb0 : bb1) + b_off[i]),
+                                             (lptr_t)(lb + dma_off + i * 1024), 16, 0, 0);
+        }
+    };
 
-    u32x4 ra[4], rb[4];
+    // ---- operand addressing ------------------------------------------------------------------
+    // fragment of 32 rows x 16 k: lane reads row (lane & 31), logical piece kk*2 + lane/32
+    const int lr = lane & 31;
+    int frag_off[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        ra[i] = *reinterpret_cast<const u32x4*>(ga[i]);
-        rb[i] = *reinterpret_cast<const u32x4*>(gb[i]);
-    }
-    const int nkt = K / kBK;
-    for (int kt = 0; kt < nkt; ++kt) {
+    for (int kk = 0; kk < 4; ++kk) frag_off[kk] = lr * 128 + (((kk * 2 + (lane >> 5)) ^ ((lr >> 1) & 7)) << 4);
+
+    f32x16 acc[8][2];  // [token tile][weight-row tile]
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<u32x4*>(lds_a + la[i]) = ra[i];
-            *reinterpret_cast<u32x4*>(lds_b + la[i]) = rb[i];
-        }
-        __syncthreads();
-        if (kt + 1 < nkt) {
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                ra[i] = *reinterpret_cast<const u32x4*>(ga[i] + (size_t)(kt + 1) * kBK);
-                rb[i] = *reinterpret_cast<const u32x4*>(gb[i] + (size_t)(kt + 1) * kBK);
-            }
-        }
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int pc = kk * 2 + (lane >> 5);
-            bf16x8 fa[2], fb[2];
+            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
+
+    struct Frags {
+        bf16x8 b[2], a[8];
+    };
+    auto load_frags = [&](Frags& fr, const char* la, const char* lb, int kk) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                fa[j] = *reinterpret_cast<const bf16x8*>(lds_a + swz(wm * 64 + j * 32 + (lane & 31), pc));
+        for (int i = 0; i < 2; ++i)
+            fr.b[i] = *reinterpret_cast<const bf16x8*>(lb + (wave * 64 + i * 32) * 128 + frag_off[kk]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) fr.a[j] = *reinterpret_cast<const bf16x8*>(la + j * 32 * 128 + frag_off[kk]);
+    };
+    auto mma = [&](const Frags& fr) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-                fb[i] = *reinterpret_cast<const bf16x8*>(lds_b + swz(wn * 64 + i * 32 + (lane & 31), pc));
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
-        }
-        __syncthreads();
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.b[i], fr.a[j], acc[j][i], 0, 0, 0);
+    };
+// scheduling hints: one LDS read (and one DMA issue) in the shadow of each matrix instruction
+#define MMOE_SCHED_MMA_LDS()                                      \
+    _Pragma("unroll") for (int q_ = 0; q_ < 10; ++q_) {           \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
+    }                                                             \
+    __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+#define MMOE_SCHED_MMA_LDS_DMA()                                  \
+    _Pragma("unroll") for (int q_ = 0; q_ < 10; ++q_) {           \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);        \
+    }                                                             \
+    _Pragma("unroll") for (int q_ = 0; q_ < 6; ++q_) {            \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);        \
     }
 
+    // Pipeline.  Stage 0 holds even k steps, stage 1 odd ones.  While k step t is multiplied
+    // the DMA of step t+1 is in flight; operand fragments are fetched one 16-k slice ahead of
+    // the matrix instructions that use them; the barrier sits before the last slice so that
+    // the first fragments of the next step are fetched in its shadow.
+    const int nkt = K / kBK;  // even: K is a multiple of 256
+    const int last = nkt - 1;
+    Frags f0, f1;
+    issue(lds_a0, lds_b0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    __syncthreads();
+    issue(lds_a1, lds_b1, 1);
+    load_frags(f0, lds_a0, lds_b0, 0);
+    for (int kt = 0; kt < nkt; kt += 2) {
+        // k step kt from stage 0
+        load_frags(f1, lds_a0, lds_b0, 1);
+        mma(f0);
+        MMOE_SCHED_MMA_LDS()
+        load_frags(f0, lds_a0, lds_b0, 2);
+        mma(f1);
+        MMOE_SCHED_MMA_LDS()
+        load_frags(f1, lds_a0, lds_b0, 3);
+        mma(f0);
+        MMOE_SCHED_MMA_LDS()
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        __syncthreads();  // step kt+1 has landed in stage 1; nobody reads stage 0 any more
+        issue(lds_a0, lds_b0, min(kt + 2, last));  // past the end: a harmless reload of the last step
+        load_frags(f0, lds_a1, lds_b1, 0);
+        mma(f1);
+        MMOE_SCHED_MMA_LDS_DMA()
+        // k step kt+1 from stage 1
+        load_frags(f1, lds_a1, lds_b1, 1);
+        mma(f0);
+        MMOE_SCHED_MMA_LDS()
+        load_frags(f0, lds_a1, lds_b1, 2);
+        mma(f1);
+        MMOE_SCHED_MMA_LDS()
+        load_frags(f1, lds_a1, lds_b1, 3);
+        mma(f0);
+        MMOE_SCHED_MMA_LDS()
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        __syncthreads();  // step kt+2 has landed in stage 0; nobody reads stage 1 any more
+        issue(lds_a1, lds_b1, min(kt + 3, last));
+        load_frags(f0, lds_a0, lds_b0, 0);
+        mma(f1);
+        MMOE_SCHED_MMA_LDS_DMA()
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);  // drain the trailing reloads before the workgroup ends
+#undef MMOE_SCHED_MMA_LDS
+#undef MMOE_SCHED_MMA_LDS_DMA
+
+    // ---- epilogue -------------------------------------------------------------------------------
     // accumulator element e of lane l: weight row 8*(e/4) + 4*(l/32) + e%4, token column l%32
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int row = m0 + wm * 64 + j * 32 + (lane & 31);
+    for (int j = 0; j < 8; ++j) {
+        const int row = m0 + j * 32 + lr;
         if (row >= cnt) continue;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -155,27 +263,27 @@ __global__ __launch_bounds__(kTThreads) void tiled_kernel(const uint16_t* __rest
             if (MODE == kTModeSwigluH) {
                 float o[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = silu_mul_t(acc[0][j][4 * q + e], acc[1][j][4 * q + e]);
+                for (int e = 0; e < 4; ++e) o[e] = silu_mul_t(acc[j][0][4 * q + e], acc[j][1][4 * q + e]);
                 u32x2 pk;
                 pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
                 pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
-                const size_t at = (size_t)(r0 + row) * N + n0 + wn * 32 + sub;
+                const size_t at = (size_t)(r0 + row) * N + n0 + wave * 32 + sub;
                 *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) = pk;
             } else {
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const size_t at = (size_t)(r0 + row) * N + n0 + wn * 64 + i * 32 + sub;
+                    const size_t at = (size_t)(r0 + row) * N + n0 + wave * 64 + i * 32 + sub;
                     if (MODE == kTModeReluH) {
                         float o[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = fmaxf(acc[i][j][4 * q + e], 0.0f);
+                        for (int e = 0; e < 4; ++e) o[e] = fmaxf(acc[j][i][4 * q + e], 0.0f);
                         u32x2 pk;
                         pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
                         pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
                         *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) = pk;
                     } else {
                         *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) =
-                            f32x4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                            f32x4{acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2], acc[j][i][4 * q + 3]};
                     }
                 }
             }
@@ -183,23 +291,32 @@ __global__ __launch_bounds__(kTThreads) void tiled_kernel(const uint16_t* __rest
     }
 }
 
+size_t tiled_table_bytes(const mmoe_shape& s) { return align256((size_t)(s.S + 2) * 4); }
+
 int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                     const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
+                     const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab, hipStream_t st,
+                     hipEvent_t mid)
 {
     if (s.dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     const int P = s.T * s.top_k, d = s.d_model, f = s.d_ff;
     const int mtiles = (P + kBM - 1) / kBM + s.S;  // upper bound of sum_s ceil(count_s / kBM)
+    auto grid_for = [&](int nt) { return dim3((unsigned)(((size_t)mtiles * nt + kXcds - 1) / kXcds * kXcds)); };
     dim3 block(kTThreads);
     const uint16_t* nul = nullptr;
-    if (s.act == MMOE_SWIGLU)
-        hipLaunchKernelGGL(tiled_kernel<kTModeSwigluH>, dim3(mtiles, f / (kBN / 2)), block, 0, st,
-                           (const uint16_t*)Xg, offsets, (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, s.S);
-    else
-        hipLaunchKernelGGL(tiled_kernel<kTModeReluH>, dim3(mtiles, f / kBN), block, 0, st, (const uint16_t*)Xg,
-                           offsets, (const uint16_t*)W1p, nul, H, d, f, s.S);
+    hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S);
+    if (s.act == MMOE_SWIGLU) {
+        const int nt = f / (kBN / 2);
+        hipLaunchKernelGGL(tiled_kernel<kTModeSwigluH>, grid_for(nt), block, 0, st, (const uint16_t*)Xg, offsets, tab,
+                           (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, s.S, nt);
+    } else {
+        const int nt = f / kBN;
+        hipLaunchKernelGGL(tiled_kernel<kTModeReluH>, grid_for(nt), block, 0, st, (const uint16_t*)Xg, offsets, tab,
+                           (const uint16_t*)W1p, nul, H, d, f, s.S, nt);
+    }
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    hipLaunchKernelGGL(tiled_kernel<kTModePlainF32>, dim3(mtiles, d / kBN), block, 0, st, (const uint16_t*)H,
-                       offsets, (const uint16_t*)W2p, nul, (void*)Yg, f, d, s.S);
+    const int nt2 = d / kBN;
+    hipLaunchKernelGGL(tiled_kernel<kTModePlainF32>, grid_for(nt2), block, 0, st, (const uint16_t*)H, offsets, tab,
+                       (const uint16_t*)W2p, nul, (void*)Yg, f, d, s.S, nt2);
     return launch_status();
 }
 

@@ -36,6 +36,7 @@ WsLayout ws_layout(const mmoe_shape& s)
     L.inv_perm = take(P * 4);
     L.blk_counts = take((size_t)L.nblk * s.S * 4);
     L.blk_base = take((size_t)L.nblk * s.S * 4);
+    L.tile_tab = take(tiled_table_bytes(s));
     L.Xg = take(P * s.d_model * es);
     L.H = take(P * s.d_ff * es);
     L.Yg = take(P * s.d_model * 4);
@@ -138,14 +139,15 @@ int mmoe_expert_ffn(const mmoe_shape* shape, const void* Xg, const int32_t* offs
     if (rc) return rc;
     if (!Xg || !offsets || !W1p || !W2p || !Yg) return MMOE_ERR_NULL;
     if ((shape->act == MMOE_SWIGLU) != (W3p != nullptr)) return MMOE_ERR_W3;
-    size_t need = (size_t)shape->T * shape->top_k * shape->d_ff * elem_size(shape->dtype);
+    const size_t h_bytes = align256((size_t)shape->T * shape->top_k * shape->d_ff * elem_size(shape->dtype));
+    const size_t need = h_bytes + tiled_table_bytes(*shape);
     if (!ws || ws_bytes < need) return MMOE_ERR_WORKSPACE;
     if (misaligned(ws, 256) || misaligned(Xg, 16) || misaligned(W1p, 16) || misaligned(W3p, 16) ||
         misaligned(W2p, 16) || misaligned(Yg, 16) || misaligned(offsets, 4))
         return MMOE_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     if (use_skinny(*shape)) return launch_ffn_skinny(*shape, Xg, offsets, W1p, W3p, W2p, ws, Yg, st);
-    return launch_ffn_tiled(*shape, Xg, offsets, W1p, W3p, W2p, ws, Yg, st);
+    return launch_ffn_tiled(*shape, Xg, offsets, W1p, W3p, W2p, ws, Yg, (int32_t*)((char*)ws + h_bytes), st);
 }
 
 int mmoe_combine(const mmoe_shape* shape, const float* Yg, const int32_t* inv_perm, const float* topk_w,
@@ -198,7 +200,8 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
     if (use_skinny(*shape))
         rc = launch_ffn_skinny(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, st, mid);
     else
-        rc = launch_ffn_tiled(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, st, mid);
+        rc = launch_ffn_tiled(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, (int32_t*)(w + L.tile_tab), st,
+                              mid);
     if (rc) return rc;
     if ((rc = mark(MMOE_EV_FFN_DOWN))) return rc;
     if ((rc = launch_combine(*shape, Yg, inv_perm, topk_w, Y, st))) return rc;

@@ -37,7 +37,7 @@ inline size_t elem_size(int dtype) { return dtype == MMOE_BF16 ? 2 : 4; }
 
 // Sub-buffers of the caller's workspace used by mmoe_layer_forward (byte offsets).
 struct WsLayout {
-    size_t topk_idx, topk_w, slot, counts, offsets, perm, inv_perm, blk_counts, blk_base, Xg, H, Yg, total;
+    size_t topk_idx, topk_w, slot, counts, offsets, perm, inv_perm, blk_counts, blk_base, tile_tab, Xg, H, Yg, total;
     int nblk;
 };
 WsLayout ws_layout(const mmoe_shape& s);
@@ -59,9 +59,11 @@ int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const
 int launch_ffn_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
                       const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
                       hipEvent_t mid = nullptr);
+// `tab`: tiled_table_bytes() of scratch for the row-tile table.
 int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                     const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
+                     const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab, hipStream_t st,
                      hipEvent_t mid = nullptr);
+size_t tiled_table_bytes(const mmoe_shape& s);
 int launch_combine(const mmoe_shape& s, const float* Yg, const int32_t* inv_perm, const float* topk_w,
                    void* Y, hipStream_t st);
 int launch_pack(const mmoe_shape& s, const void* W1, const void* W3, const void* W2, void* W1p, void* W3p,
