@@ -210,7 +210,8 @@ def main():
         "config": {"workload": cfg.name, "T": cfg.T, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "V": cfg.V,
                    "E": cfg.E, "top_k": cfg.top_k, "S": S, "act": cfg.act, "seed": cfg.seed,
                    "slot_rows_min_med_max": [int(res["counts"].min()), int(sorted(res["counts"])[S // 2]),
-                                             int(res["counts"].max())]},
+                                             int(res["counts"].max())],
+                   "slot_rows": [int(c) for c in res["counts"]]},
         "layer_tflops": layer_flops / (ms * 1e-3) / 1e12,
         "stages_ms": res["stages_ms"],
         "roofline": roofline(cfg, res, skinny),

@@ -23,9 +23,11 @@
 // preparation kernel turns them into a table of row tiles; the product kernels map their
 // workgroup id to (slot, row tile, feature tile) through that table, so the host never
 // waits for the histogram.  Workgroup ids are dealt round-robin to the 8 XCDs by the
-// hardware; the id -> tile map gives each XCD a contiguous run of tiles ordered
+// hardware; the id -> tile map gives XCD x the feature tiles nt with nt mod 8 == x, ordered
 // (slot, feature tile, row tile), so the workgroups resident on one XCD share weight and
-// activation panels in that XCD's L2.
+// activation panels in that XCD's L2 and every XCD sees the same mix of row tiles.
+#include <type_traits>
+
 #include "mmoe_internal.h"
 
 namespace mmoe {
@@ -89,21 +91,24 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
     __shared__ __attribute__((aligned(1024))) char lds_b1[kTileBytes];
 
     // ---- workgroup id -> tile ------------------------------------------------------------
-    const int total = tab[0] * NT;
-    const int chunk = (total + kXcds - 1) / kXcds;
+    // XCD x (= workgroup id mod 8) owns the feature tiles nt with nt mod 8 == x, for every slot
+    // and row tile: every XCD gets the same mix of full and partial row tiles, and all row
+    // tiles that share a weight panel run on the XCD whose L2 holds it.  Inside an XCD the
+    // order is (slot, feature tile, row tile), row tile fastest.
+    const int total_m = tab[0];
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
-    const int L = xcd * chunk + local;
-    if (local >= chunk || L >= total) return;  // uniform over the workgroup
-    // slot s with tab[1+s]*NT <= L < tab[2+s]*NT (binary search; empty slots have equal bounds)
+    const int nt_x = (NT - xcd + kXcds - 1) / kXcds;  // feature tiles owned by this XCD
+    if (local >= total_m * nt_x) return;              // uniform over the workgroup
+    // slot s with tab[1+s]*nt_x <= local < tab[2+s]*nt_x (binary search; empty slots have equal bounds)
     int lo = 0, hi = S;
     while (hi - lo > 1) {
         int mid = (lo + hi) >> 1;
-        if (tab[1 + mid] * NT <= L) lo = mid; else hi = mid;
+        if (tab[1 + mid] * nt_x <= local) lo = mid; else hi = mid;
     }
     const int s = lo;
     const int mt_s = tab[2 + s] - tab[1 + s];   // row tiles of this slot (> 0 by construction)
-    const int rem = L - tab[1 + s] * NT;
-    const int nt = rem / mt_s, mi = rem % mt_s;  // row tile fastest
+    const int rem = local - tab[1 + s] * nt_x;
+    const int nt = (rem / mt_s) * kXcds + xcd, mi = rem % mt_s;  // row tile fastest
     const int m0 = mi * kBM;
     const int r0 = offsets[s];
     const int cnt = offsets[s + 1] - r0;
@@ -166,90 +171,103 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
 
-    struct Frags {
-        bf16x8 b[2], a[8];
-    };
-    auto load_frags = [&](Frags& fr, const char* la, const char* lb, int kk) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            fr.b[i] = *reinterpret_cast<const bf16x8*>(lb + (wave * 64 + i * 32) * 128 + frag_off[kk]);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) fr.a[j] = *reinterpret_cast<const bf16x8*>(la + j * 32 * 128 + frag_off[kk]);
-    };
-    auto mma = [&](const Frags& fr) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.b[i], fr.a[j], acc[j][i], 0, 0, 0);
-    };
-// scheduling hints: one LDS read (and one DMA issue) in the shadow of each matrix instruction
-#define MMOE_SCHED_MMA_LDS()                                      \
-    _Pragma("unroll") for (int q_ = 0; q_ < 10; ++q_) {           \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
-    }                                                             \
-    __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
-#define MMOE_SCHED_MMA_LDS_DMA()                                  \
-    _Pragma("unroll") for (int q_ = 0; q_ < 10; ++q_) {           \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);        \
-    }                                                             \
-    _Pragma("unroll") for (int q_ = 0; q_ < 6; ++q_) {            \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);        \
-    }
-
-    // Pipeline.  Stage 0 holds even k steps, stage 1 odd ones.  While k step t is multiplied
-    // the DMA of step t+1 is in flight; operand fragments are fetched one 16-k slice ahead of
-    // the matrix instructions that use them; the barrier sits before the last slice so that
-    // the first fragments of the next step are fetched in its shadow.
+    // Main loop, instantiated for NJ = number of 32-row token sub-tiles that hold rows (8 for
+    // every tile but the last one of a slot).  Stage 0 holds even k steps, stage 1 odd ones.
+    // While k step t is multiplied the DMA of step t+1 is in flight; operand fragments are
+    // fetched one 16-k slice ahead of the matrix instructions that use them; the barrier sits
+    // before the last slice so that the first fragments of the next step are fetched in its
+    // shadow.  The scheduling hints put one LDS read (and one DMA issue) in the shadow of each
+    // matrix instruction.
     const int nkt = K / kBK;  // even: K is a multiple of 256
     const int last = nkt - 1;
-    Frags f0, f1;
-    issue(lds_a0, lds_b0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-    __syncthreads();
-    issue(lds_a1, lds_b1, 1);
-    load_frags(f0, lds_a0, lds_b0, 0);
-    for (int kt = 0; kt < nkt; kt += 2) {
-        // k step kt from stage 0
-        load_frags(f1, lds_a0, lds_b0, 1);
-        mma(f0);
-        MMOE_SCHED_MMA_LDS()
-        load_frags(f0, lds_a0, lds_b0, 2);
-        mma(f1);
-        MMOE_SCHED_MMA_LDS()
-        load_frags(f1, lds_a0, lds_b0, 3);
-        mma(f0);
-        MMOE_SCHED_MMA_LDS()
-        __builtin_amdgcn_s_waitcnt(0x0070);
-        __syncthreads();  // step kt+1 has landed in stage 1; nobody reads stage 0 any more
-        issue(lds_a0, lds_b0, min(kt + 2, last));  // past the end: a harmless reload of the last step
-        load_frags(f0, lds_a1, lds_b1, 0);
-        mma(f1);
-        MMOE_SCHED_MMA_LDS_DMA()
-        // k step kt+1 from stage 1
-        load_frags(f1, lds_a1, lds_b1, 1);
-        mma(f0);
-        MMOE_SCHED_MMA_LDS()
-        load_frags(f0, lds_a1, lds_b1, 2);
-        mma(f1);
-        MMOE_SCHED_MMA_LDS()
-        load_frags(f1, lds_a1, lds_b1, 3);
-        mma(f0);
-        MMOE_SCHED_MMA_LDS()
-        __builtin_amdgcn_s_waitcnt(0x0070);
-        __syncthreads();  // step kt+2 has landed in stage 0; nobody reads stage 1 any more
-        issue(lds_a1, lds_b1, min(kt + 3, last));
+    auto run = [&](auto njc) {
+        constexpr int NJ = decltype(njc)::value;
+        constexpr int NR = 2 + NJ, NM = 2 * NJ;
+        struct Frags {
+            bf16x8 b[2], a[NJ];
+        };
+        auto load_frags = [&](Frags& fr, const char* la, const char* lb, int kk) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                fr.b[i] = *reinterpret_cast<const bf16x8*>(lb + (wave * 64 + i * 32) * 128 + frag_off[kk]);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                fr.a[j] = *reinterpret_cast<const bf16x8*>(la + j * 32 * 128 + frag_off[kk]);
+        };
+        auto mma = [&](const Frags& fr) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.b[i], fr.a[j], acc[j][i], 0, 0, 0);
+        };
+        auto sched = [&]() {
+#pragma unroll
+            for (int q = 0; q < (NM > NR ? NM : NR); ++q) {
+                if (q < NM) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        };
+        auto sched_dma = [&]() {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                if (q < NM) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
+        };
+        Frags f0, f1;
+        issue(lds_a0, lds_b0, 0);
+        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+        __syncthreads();
+        issue(lds_a1, lds_b1, 1);
         load_frags(f0, lds_a0, lds_b0, 0);
-        mma(f1);
-        MMOE_SCHED_MMA_LDS_DMA()
+        for (int kt = 0; kt < nkt; kt += 2) {
+            // k step kt from stage 0
+            load_frags(f1, lds_a0, lds_b0, 1);
+            mma(f0);
+            sched();
+            load_frags(f0, lds_a0, lds_b0, 2);
+            mma(f1);
+            sched();
+            load_frags(f1, lds_a0, lds_b0, 3);
+            mma(f0);
+            sched();
+            __builtin_amdgcn_s_waitcnt(0x0070);
+            __syncthreads();  // step kt+1 has landed in stage 1; nobody reads stage 0 any more
+            issue(lds_a0, lds_b0, min(kt + 2, last));  // past the end: a harmless reload of the last step
+            load_frags(f0, lds_a1, lds_b1, 0);
+            mma(f1);
+            sched_dma();
+            // k step kt+1 from stage 1
+            load_frags(f1, lds_a1, lds_b1, 1);
+            mma(f0);
+            sched();
+            load_frags(f0, lds_a1, lds_b1, 2);
+            mma(f1);
+            sched();
+            load_frags(f1, lds_a1, lds_b1, 3);
+            mma(f0);
+            sched();
+            __builtin_amdgcn_s_waitcnt(0x0070);
+            __syncthreads();  // step kt+2 has landed in stage 0; nobody reads stage 1 any more
+            issue(lds_a1, lds_b1, min(kt + 3, last));
+            load_frags(f0, lds_a0, lds_b0, 0);
+            mma(f1);
+            sched_dma();
+        }
+        __builtin_amdgcn_s_waitcnt(0x0070);  // drain the trailing reloads before the workgroup ends
+    };
+    switch (min(8, (cnt - m0 + 31) / 32)) {
+        case 8: run(std::integral_constant<int, 8>{}); break;
+        case 7: run(std::integral_constant<int, 7>{}); break;
+        case 6: run(std::integral_constant<int, 6>{}); break;
+        case 5: run(std::integral_constant<int, 5>{}); break;
+        case 4: run(std::integral_constant<int, 4>{}); break;
+        case 3: run(std::integral_constant<int, 3>{}); break;
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        default: run(std::integral_constant<int, 1>{}); break;
     }
-    __builtin_amdgcn_s_waitcnt(0x0070);  // drain the trailing reloads before the workgroup ends
-#undef MMOE_SCHED_MMA_LDS
-#undef MMOE_SCHED_MMA_LDS_DMA
 
     // ---- epilogue -------------------------------------------------------------------------------
     // accumulator element e of lane l: weight row 8*(e/4) + 4*(l/32) + e%4, token column l%32
@@ -300,7 +318,7 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets
     if (s.dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     const int P = s.T * s.top_k, d = s.d_model, f = s.d_ff;
     const int mtiles = (P + kBM - 1) / kBM + s.S;  // upper bound of sum_s ceil(count_s / kBM)
-    auto grid_for = [&](int nt) { return dim3((unsigned)(((size_t)mtiles * nt + kXcds - 1) / kXcds * kXcds)); };
+    auto grid_for = [&](int nt) { return dim3((unsigned)((size_t)mtiles * ((nt + kXcds - 1) / kXcds) * kXcds)); };
     dim3 block(kTThreads);
     const uint16_t* nul = nullptr;
     hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S);
