@@ -44,14 +44,51 @@ constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-__device__ __forceinline__ float silu_mul_t(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+// silu(g) * u with the hardware exponential and reciprocal (about 1 ulp each; the result is
+// rounded to bf16 right after).  A full-precision division here costs more matrix-core idle
+// time at the end of every tile than it is worth.
+__device__ __forceinline__ float silu_mul_t(float g, float u)
+{
+    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+}
 
-// Table written by tile_table_kernel: tab[0] = number of row tiles; tab[1 + s] = first row
-// tile of slot s (tab[1 + S] = number of row tiles again).
+// Tile lists written by tile_table_kernel, one workgroup, from the device-side `offsets`:
+//   tab[0]                      number of row tiles, sum_s ceil(count_s / 256)
+//   four lists of int4 entries  {slot, feature tile within the XCD, first row, rows valid},
+//   one per (product, feature tiles per XCD): a product with NT feature tiles gives XCD x
+//   the tiles nt with nt mod 8 == x, that is ceil or floor of NT/8 of them; list entry
+//   `local` is the tile that the workgroup with id 8*local + x computes, in the order
+//   (slot, feature tile, row tile), row tile fastest.
+struct TileLists {
+    int hdr;        // int32 index of tab[0]
+    int list[2][2]; // [product: up, down][0: ceil(NT/8) per XCD, 1: floor] -> int4 index into tab
+    int cap[2];     // entries reserved per list of each product
+    size_t bytes;
+};
+
+static TileLists tile_lists(int P, int S, int nt_up, int nt_down)
+{
+    TileLists L;
+    const int mt = (P + kBM - 1) / kBM + S;  // upper bound of the number of row tiles
+    L.hdr = 0;
+    L.cap[0] = mt * ((nt_up + kXcds - 1) / kXcds);
+    L.cap[1] = mt * ((nt_down + kXcds - 1) / kXcds);
+    int at = 16;  // int4 units; the header takes the first 256 bytes
+    for (int p = 0; p < 2; ++p)
+        for (int c = 0; c < 2; ++c) {
+            L.list[p][c] = at;
+            at += L.cap[p];
+        }
+    L.bytes = (size_t)at * 16;
+    return L;
+}
+
 __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restrict__ offsets,
-                                                         int32_t* __restrict__ tab, int S)
+                                                         int32_t* __restrict__ tab, int S, int nt_up, int nt_down,
+                                                         TileLists L)
 {
     __shared__ int part[256];
+    __shared__ int base[kMaxS + 1];  // first row tile of each slot
     // thread t covers slots [t*per, (t+1)*per)
     const int per = (S + 255) / 256;
     const int s_lo = min((int)threadIdx.x * per, S), s_hi = min(s_lo + per, S);
@@ -66,24 +103,45 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
             part[t] = run;
             run += c;
         }
-        tab[0] = run;
-        tab[1 + S] = run;
+        tab[L.hdr] = run;
+        base[S] = run;
     }
     __syncthreads();
     int run = part[threadIdx.x];
     for (int s = s_lo; s < s_hi; ++s) {
-        tab[1 + s] = run;
+        base[s] = run;
         run += (offsets[s + 1] - offsets[s] + kBM - 1) / kBM;
+    }
+    __syncthreads();
+    const int total_m = base[S];
+    int4* lists = reinterpret_cast<int4*>(tab);
+    for (int p = 0; p < 2; ++p) {
+        const int NT = p == 0 ? nt_up : nt_down;
+        for (int c = 0; c < 2; ++c) {
+            const int nt_x = c == 0 ? (NT + kXcds - 1) / kXcds : NT / kXcds;
+            const int n = total_m * nt_x;
+            for (int e = threadIdx.x; e < n; e += 256) {
+                int lo = 0, hi = S;  // largest s with base[s]*nt_x <= e (empty slots have equal bounds)
+                while (hi - lo > 1) {
+                    int mid = (lo + hi) >> 1;
+                    if (base[mid] * nt_x <= e) lo = mid; else hi = mid;
+                }
+                const int s = lo, mt_s = base[s + 1] - base[s];
+                const int rem = e - base[s] * nt_x;
+                const int ntl = rem / mt_s, mi = rem % mt_s;
+                const int r0 = offsets[s], cnt = offsets[s + 1] - r0;
+                lists[L.list[p][c] + e] = make_int4(s, ntl, r0 + mi * kBM, min(kBM, cnt - mi * kBM));
+            }
+        }
     }
 }
 
 template <int MODE>
 __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __restrict__ A,
-                                                             const int32_t* __restrict__ offsets,
-                                                             const int32_t* __restrict__ tab,
-                                                             const uint16_t* __restrict__ W0,
+                                                             const int32_t* __restrict__ tab, int list_hi,
+                                                             int list_lo, const uint16_t* __restrict__ W0,
                                                              const uint16_t* __restrict__ W1,
-                                                             void* __restrict__ out, int K, int N, int S, int NT)
+                                                             void* __restrict__ out, int K, int N, int NT)
 {
     __shared__ __attribute__((aligned(1024))) char lds_a0[kTileBytes];
     __shared__ __attribute__((aligned(1024))) char lds_b0[kTileBytes];
@@ -93,25 +151,19 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
     // ---- workgroup id -> tile ------------------------------------------------------------
     // XCD x (= workgroup id mod 8) owns the feature tiles nt with nt mod 8 == x, for every slot
     // and row tile: every XCD gets the same mix of full and partial row tiles, and all row
-    // tiles that share a weight panel run on the XCD whose L2 holds it.  Inside an XCD the
-    // order is (slot, feature tile, row tile), row tile fastest.
-    const int total_m = tab[0];
+    // tiles that share a weight panel run on the XCD whose L2 holds it.  One 16-byte entry of
+    // the prepared list says which tile this workgroup computes.
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
     const int nt_x = (NT - xcd + kXcds - 1) / kXcds;  // feature tiles owned by this XCD
+    const int4* list = reinterpret_cast<const int4*>(tab) + (nt_x == (NT + kXcds - 1) / kXcds ? list_hi : list_lo);
+    const int total_m = tab[0];
+    const int4 ent = list[local];                     // in bounds for every workgroup of the grid
     if (local >= total_m * nt_x) return;              // uniform over the workgroup
-    // slot s with tab[1+s]*nt_x <= local < tab[2+s]*nt_x (binary search; empty slots have equal bounds)
-    int lo = 0, hi = S;
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (tab[1 + mid] * nt_x <= local) lo = mid; else hi = mid;
-    }
-    const int s = lo;
-    const int mt_s = tab[2 + s] - tab[1 + s];   // row tiles of this slot (> 0 by construction)
-    const int rem = local - tab[1 + s] * nt_x;
-    const int nt = (rem / mt_s) * kXcds + xcd, mi = rem % mt_s;  // row tile fastest
-    const int m0 = mi * kBM;
-    const int r0 = offsets[s];
-    const int cnt = offsets[s + 1] - r0;
+    const int s = ent.x;
+    const int nt = ent.y * kXcds + xcd;
+    const int r0 = ent.z;                             // first row of the tile
+    const int cnt = ent.w;                            // rows of the tile that exist (1..256)
+    const int m0 = 0;
 
     constexpr int kFeat = MODE == kTModeSwigluH ? kBN / 2 : kBN;  // output features per tile
     const int n0 = nt * kFeat;
@@ -309,7 +361,18 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
     }
 }
 
-size_t tiled_table_bytes(const mmoe_shape& s) { return align256((size_t)(s.S + 2) * 4); }
+static void tiled_nts(const mmoe_shape& s, int& nt_up, int& nt_down)
+{
+    nt_up = s.act == MMOE_SWIGLU ? s.d_ff / (kBN / 2) : s.d_ff / kBN;
+    nt_down = s.d_model / kBN;
+}
+
+size_t tiled_table_bytes(const mmoe_shape& s)
+{
+    int nt_up, nt_down;
+    tiled_nts(s, nt_up, nt_down);
+    return align256(tile_lists(s.T * s.top_k, s.S, nt_up, nt_down).bytes);
+}
 
 int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
                      const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab, hipStream_t st,
@@ -317,24 +380,22 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets
 {
     if (s.dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     const int P = s.T * s.top_k, d = s.d_model, f = s.d_ff;
-    const int mtiles = (P + kBM - 1) / kBM + s.S;  // upper bound of sum_s ceil(count_s / kBM)
-    auto grid_for = [&](int nt) { return dim3((unsigned)((size_t)mtiles * ((nt + kXcds - 1) / kXcds) * kXcds)); };
+    if ((int64_t)P * (d > f ? d : f) >= ((int64_t)1 << 31)) return MMOE_ERR_LIMIT;  // 32-bit byte offsets inside a panel
+    int nt_up, nt_down;
+    tiled_nts(s, nt_up, nt_down);
+    const TileLists L = tile_lists(P, s.S, nt_up, nt_down);
     dim3 block(kTThreads);
     const uint16_t* nul = nullptr;
-    hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S);
-    if (s.act == MMOE_SWIGLU) {
-        const int nt = f / (kBN / 2);
-        hipLaunchKernelGGL(tiled_kernel<kTModeSwigluH>, grid_for(nt), block, 0, st, (const uint16_t*)Xg, offsets, tab,
-                           (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, s.S, nt);
-    } else {
-        const int nt = f / kBN;
-        hipLaunchKernelGGL(tiled_kernel<kTModeReluH>, grid_for(nt), block, 0, st, (const uint16_t*)Xg, offsets, tab,
-                           (const uint16_t*)W1p, nul, H, d, f, s.S, nt);
-    }
+    hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, L);
+    if (s.act == MMOE_SWIGLU)
+        hipLaunchKernelGGL(tiled_kernel<kTModeSwigluH>, dim3(L.cap[0] * kXcds), block, 0, st, (const uint16_t*)Xg, tab,
+                           L.list[0][0], L.list[0][1], (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, nt_up);
+    else
+        hipLaunchKernelGGL(tiled_kernel<kTModeReluH>, dim3(L.cap[0] * kXcds), block, 0, st, (const uint16_t*)Xg, tab,
+                           L.list[0][0], L.list[0][1], (const uint16_t*)W1p, nul, H, d, f, nt_up);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    const int nt2 = d / kBN;
-    hipLaunchKernelGGL(tiled_kernel<kTModePlainF32>, grid_for(nt2), block, 0, st, (const uint16_t*)H, offsets, tab,
-                       (const uint16_t*)W2p, nul, (void*)Yg, f, d, s.S, nt2);
+    hipLaunchKernelGGL(tiled_kernel<kTModePlainF32>, dim3(L.cap[1] * kXcds), block, 0, st, (const uint16_t*)H, tab,
+                       L.list[1][0], L.list[1][1], (const uint16_t*)W2p, nul, (void*)Yg, f, d, nt_down);
     return launch_status();
 }
 
