@@ -322,40 +322,52 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
     }
 
     // ---- epilogue -------------------------------------------------------------------------------
-    // accumulator element e of lane l: weight row 8*(e/4) + 4*(l/32) + e%4, token column l%32
+    // Accumulator element e of lane l is weight row 8*(e/4) + 4*(l/32) + e%4 of token column
+    // l%32: a lane holds scattered 4-feature groups of one token.  Each wavefront therefore
+    // passes its results through a private LDS patch, 32 tokens x 32 features at a time, and
+    // reads them back row by row, so that every global store instruction writes whole
+    // contiguous row segments (128 bytes for fp32 output, 64 for bf16).
+    constexpr int kEsz = MODE == kTModePlainF32 ? 4 : 2;
+    constexpr int kRowB = 32 * kEsz;                  // bytes of one staged row
+    constexpr int kPitch = kRowB + 16;                // padded: conflict-free 16-byte column writes
+    constexpr int kLpr = kRowB / 16;                  // lanes that read one row back
+    constexpr int kRpi = 64 / kLpr;                   // rows per read-back instruction
+    constexpr int kChunks = MODE == kTModeSwigluH ? 1 : 2;  // 32-feature chunks per wavefront
+    __shared__ __attribute__((aligned(16))) char lds_epi[4][32 * (32 * 4 + 16)];
+    char* ebuf = lds_epi[wave];
+    char* const obase = reinterpret_cast<char*>(out) +
+                        ((size_t)r0 * N + n0 + wave * (32 * kChunks)) * kEsz + (size_t)(lane / kLpr) * N * kEsz +
+                        (lane % kLpr) * 16;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const int row = m0 + j * 32 + lr;
-        if (row >= cnt) continue;
+        if (j * 32 >= cnt) break;  // uniform
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int sub = 8 * q + 4 * (lane >> 5);
-            if (MODE == kTModeSwigluH) {
+        for (int c = 0; c < kChunks; ++c) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
                 float o[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = silu_mul_t(acc[j][0][4 * q + e], acc[j][1][4 * q + e]);
-                u32x2 pk;
-                pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
-                pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
-                const size_t at = (size_t)(r0 + row) * N + n0 + wave * 32 + sub;
-                *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) = pk;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const size_t at = (size_t)(r0 + row) * N + n0 + wave * 64 + i * 32 + sub;
-                    if (MODE == kTModeReluH) {
-                        float o[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = fmaxf(acc[j][i][4 * q + e], 0.0f);
-                        u32x2 pk;
-                        pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
-                        pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
-                        *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) = pk;
-                    } else {
-                        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) =
-                            f32x4{acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2], acc[j][i][4 * q + 3]};
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    if (MODE == kTModeSwigluH) o[e] = silu_mul_t(acc[j][0][4 * q + e], acc[j][1][4 * q + e]);
+                    else if (MODE == kTModeReluH) o[e] = fmaxf(acc[j][c][4 * q + e], 0.0f);
+                    else o[e] = acc[j][c][4 * q + e];
                 }
+                char* at = ebuf + lr * kPitch + (8 * q + 4 * (lane >> 5)) * kEsz;
+                if (kEsz == 4) {
+                    *reinterpret_cast<f32x4*>(at) = f32x4{o[0], o[1], o[2], o[3]};
+                } else {
+                    u32x2 pk;
+                    pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
+                    pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
+                    *reinterpret_cast<u32x2*>(at) = pk;
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < 32 / kRpi; ++it) {
+                const int row = it * kRpi + lane / kLpr;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(ebuf + row * kPitch + (lane % kLpr) * 16);
+                if (j * 32 + row < cnt)
+                    *reinterpret_cast<u32x4*>(obase + ((size_t)(j * 32 + it * kRpi) * N + c * 32) * kEsz) = v;
             }
         }
     }
