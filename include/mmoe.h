@@ -89,9 +89,15 @@ const char *mmoe_strerror(int status);
  * One-time repacking of the pool, done when the pool is loaded (the paper's
  * loader runs once, offline, before serving: section 3.1).  The boundary's
  * plain layout is "in x out": W1, W3 [S, d, f] and W2 [S, f, d].  The expert
- * kernels read the transposed, reduction-dimension-contiguous layout
- * W1p, W3p [S, f, d] and W2p [S, d, f] that this call writes.  W3/W3p are NULL
- * for RELU.  Outputs must not overlap inputs.
+ * kernels read the packed pool that this call writes; each packed matrix has as
+ * many elements as the plain one.  With out[n] = sum_k x[k] W[k][n], N outputs, K inputs:
+ *   fp32: the transpose [S, N, K] (reduction dimension contiguous);
+ *   bf16: matrix-core fragments.  Element (n, k) of slot s is stored at
+ *         ((((s*(N/32) + n/32)*(K/16) + ks)*64 + 32*h + n%32)*8 + k%8
+ *         with m = k/64, h = (k%64)/32, kk = (k%32)/8, ks = 4*m + kk:
+ *         the 64 pieces of 16 bytes that follow each other are exactly the 32-row x 16-k
+ *         operand of v_mfma_f32_32x32x16_bf16 as its 64 lanes hold it.
+ * W3/W3p are NULL for RELU.  Outputs must not overlap inputs.
  */
 int mmoe_pack_weights(const mmoe_shape *shape, const void *W1, const void *W3, const void *W2,
                       void *W1p, void *W3p, void *W2p, void *stream);

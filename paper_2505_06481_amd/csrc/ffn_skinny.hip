@@ -10,6 +10,10 @@
 // 16 tokens are its 16 columns, so the weights pass through registers once however many
 // tokens (up to 32 per pass) the slot holds.
 //
+// The text below describes the fp32 kernel (transposed pool, 16x16x4 matrix instructions).
+// The bf16 kernel further down follows the same plan on the fragment-packed pool with
+// 32x32x16 instructions: 32 output features per workgroup, up to 32 rows per pass.
+//
 // Reduction-index permutation: per 256-byte step of a row, lane group g = lane/16 loads
 // the contiguous 64 bytes [64g, 64g+64) as four 16-byte pieces q; piece q of every group
 // feeds matrix instruction q.  Weights and activations use the same permutation, and a
@@ -178,6 +182,153 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
     }
 }
 
+// ---- bf16 on the fragment-packed pool ----------------------------------------------------
+// Workgroup = one 32-row block of weights (32 output features) of one slot, all rows of the
+// slot.  The block's fragments lie one after the other in memory (1 KB each, 16 k per
+// fragment), so the four wavefronts take runs of 4 fragments (64 k) in turn and every
+// weight load is a fully contiguous 1 KB read that goes straight into the matrix-core
+// operand registers.  Tokens are the 32-column operand: lane (token l%32, half h = l/32)
+// reads the 64 contiguous bytes of its activation row that the run's permutation assigns
+// to it.  Partial sums of the four wavefronts meet in LDS.
+template <int NW, int KU, int MODE>
+__global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t* __restrict__ A,
+                                                                 const int32_t* __restrict__ offsets,
+                                                                 const uint16_t* __restrict__ W0,
+                                                                 const uint16_t* __restrict__ W1,
+                                                                 void* __restrict__ out, int K, int N)
+{
+    __shared__ float red[kSkWaves][NW][kWave][16];  // 16 KB per matrix
+
+    const int s = blockIdx.y;
+    const int nb = blockIdx.x;
+    const int r0 = offsets[s];
+    const int cnt = offsets[s + 1] - r0;
+    if (cnt <= 0) return;  // uniform over the workgroup
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int tok = lane & 31, h = lane >> 5;
+    const int nit = K / (64 * KU);  // iterations of KU runs of 64 k
+
+    // fragment ks of this block: element offset ((s*(N/32) + nb)*(K/16) + ks)*512 + lane*8
+    const size_t blk = ((size_t)s * (N / 32) + nb) * (size_t)(K / 16) * 512 + (size_t)lane * 8;
+    const uint16_t* wrow[NW];
+    wrow[0] = W0 + blk;
+    if (NW == 2) wrow[NW - 1] = W1 + blk;
+
+    for (int pass0 = 0; pass0 < cnt; pass0 += 32) {
+        const int rr = min(pass0 + tok, cnt - 1);  // tokens past the end re-read the last one; never stored
+        const uint16_t* arow = A + (size_t)(r0 + rr) * K + h * 32;
+        f32x16 acc[NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[w][e] = 0.0f;
+
+        u32x4 wcur[NW][KU][4], wnxt[NW][KU][4];
+        int it = wave;
+        if (it < nit) {
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int u = 0; u < KU; ++u)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        wcur[w][u][q] =
+                            *reinterpret_cast<const u32x4*>(wrow[w] + ((size_t)(it * KU + u) * 4 + q) * 512);
+        }
+        for (; it < nit; it += kSkWaves) {
+            u32x4 xa[KU][4];
+#pragma unroll
+            for (int u = 0; u < KU; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    xa[u][q] = *reinterpret_cast<const u32x4*>(arow + (size_t)(it * KU + u) * 64 + q * 8);
+            const int itn = it + kSkWaves;
+            if (itn < nit) {  // the next weights: the youngest loads, still in flight during the math below
+#pragma unroll
+                for (int w = 0; w < NW; ++w)
+#pragma unroll
+                    for (int u = 0; u < KU; ++u)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            wnxt[w][u][q] =
+                                *reinterpret_cast<const u32x4*>(wrow[w] + ((size_t)(itn * KU + u) * 4 + q) * 512);
+            }
+#pragma unroll
+            for (int u = 0; u < KU; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int w = 0; w < NW; ++w)
+                        acc[w] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wcur[w][u][q]),
+                                                                         __builtin_bit_cast(bf16x8, xa[u][q]), acc[w],
+                                                                         0, 0, 0);
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int u = 0; u < KU; ++u)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) wcur[w][u][q] = wnxt[w][u][q];
+        }
+
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[wave][w][lane][e] = acc[w][e];
+        __syncthreads();
+        // accumulator element e of lane l: feature 8*(e/4) + 4*(l/32) + e%4 of token column l%32.
+        // Thread (l = tid%64, q = tid/64) finishes elements 4q .. 4q+3 of lane l: 4 consecutive features.
+        {
+            const int l = threadIdx.x & 63, q = threadIdx.x >> 6;
+            const int row = pass0 + (l & 31);
+            if (row < cnt) {
+                float o[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = 4 * q + i;
+                    float v[NW];
+#pragma unroll
+                    for (int w = 0; w < NW; ++w)
+                        v[w] = (red[0][w][l][e] + red[1][w][l][e]) + (red[2][w][l][e] + red[3][w][l][e]);
+                    if (MODE == kModeSwigluH) o[i] = silu_mul(v[0], v[NW - 1]);
+                    else if (MODE == kModeReluH) o[i] = fmaxf(v[0], 0.0f);
+                    else o[i] = v[0];
+                }
+                const size_t at = (size_t)(r0 + row) * N + nb * 32 + 8 * q + 4 * (l >> 5);
+                if (MODE == kModePlainF32) {
+                    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = f32x4{o[0], o[1], o[2], o[3]};
+                } else {
+                    u32x2 pk;
+                    pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
+                    pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
+                    *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) = pk;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+static int run_skinny_bf16(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
+                           const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
+{
+    const int d = s.d_model, f = s.d_ff;
+    dim3 block(kSkThreads);
+    dim3 g1(f / 32, s.S), g2(d / 32, s.S);
+    const uint16_t* nul = nullptr;
+    if (s.act == MMOE_SWIGLU)
+        hipLaunchKernelGGL((skinny_frag_kernel<2, 1, kModeSwigluH>), g1, block, 0, st, (const uint16_t*)Xg, offsets,
+                           (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f);
+    else
+        hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeReluH>), g1, block, 0, st, (const uint16_t*)Xg, offsets,
+                           (const uint16_t*)W1p, nul, H, d, f);
+    if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
+    hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModePlainF32>), g2, block, 0, st, (const uint16_t*)H, offsets,
+                       (const uint16_t*)W2p, nul, (void*)Yg, f, d);
+    return launch_status();
+}
+
 template <typename T>
 static int run_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
                       const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
@@ -201,7 +352,7 @@ static int run_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offset
 int launch_ffn_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
                       const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
 {
-    if (s.dtype == MMOE_BF16) return run_skinny<uint16_t>(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st, mid);
+    if (s.dtype == MMOE_BF16) return run_skinny_bf16(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st, mid);
     return run_skinny<float>(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st, mid);
 }
 

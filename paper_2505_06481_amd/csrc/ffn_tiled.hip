@@ -39,7 +39,8 @@ constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
 constexpr int kTThreads = 256;
 constexpr int kXcds = 8;
-constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB
+constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB: one step of the token operand
+constexpr int kStagesA = 3;
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -143,10 +144,7 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
                                                              const uint16_t* __restrict__ W1,
                                                              void* __restrict__ out, int K, int N, int NT)
 {
-    __shared__ __attribute__((aligned(1024))) char lds_a0[kTileBytes];
-    __shared__ __attribute__((aligned(1024))) char lds_b0[kTileBytes];
-    __shared__ __attribute__((aligned(1024))) char lds_a1[kTileBytes];
-    __shared__ __attribute__((aligned(1024))) char lds_b1[kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char lds_a[kStagesA * kTileBytes];
 
     // ---- workgroup id -> tile ------------------------------------------------------------
     // XCD x (= workgroup id mod 8) owns the feature tiles nt with nt mod 8 == x, for every slot
@@ -163,59 +161,64 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
     const int nt = ent.y * kXcds + xcd;
     const int r0 = ent.z;                             // first row of the tile
     const int cnt = ent.w;                            // rows of the tile that exist (1..256)
-    const int m0 = 0;
 
     constexpr int kFeat = MODE == kTModeSwigluH ? kBN / 2 : kBN;  // output features per tile
     const int n0 = nt * kFeat;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps LDS bases in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps bases in scalar registers
+    const int lr = lane & 31;
 
-    // ---- DMA addressing --------------------------------------------------------------------
-    // Instruction i of wavefront w fills LDS rows g*8 .. g*8+7, g = w*8 + i, of a tile: lane
-    // -> (row r = lane/8 inside the group, physical piece lane%8).  The piece fetched is the
-    // logical one that the swizzle stores there.  Addresses are a uniform 64-bit base (scalar
-    // registers, advanced by 128 bytes per k step) plus a per-lane 32-bit byte offset that
-    // never changes.
+    // ---- token operand: global -> registers -> LDS ----------------------------------------------
+    // Piece id = i*256 + tid (i < 8) of a [256 rows][8 pieces of 16 bytes] tile: 8 consecutive
+    // threads read one row's 128 contiguous bytes.  Rows past the end of the group re-read its
+    // last row (they are multiplied but never stored).
     const char* a_base = reinterpret_cast<const char*>(A) + (size_t)r0 * K * 2;
-    const char* b_base0 = reinterpret_cast<const char*>(W0) + (size_t)s * N * K * 2;
-    const char* b_base1 = MODE == kTModeSwigluH ? reinterpret_cast<const char*>(W1) + (size_t)s * N * K * 2 : b_base0;
-    uint32_t a_off[8], b_off[8];
+    uint32_t a_off[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int row = (wave * 8 + i) * 8 + (lane >> 3);
-        const int piece = (lane & 7) ^ ((row >> 1) & 7);
-        const int ar = min(m0 + row, cnt - 1);  // rows past the end re-read the last row; never stored
-        a_off[i] = (uint32_t)ar * (uint32_t)K * 2u + piece * 16;
-        int feat;
-        if (MODE == kTModeSwigluH) feat = (wave * 8 + i) / 8 * 32 + (row & 31);  // row>>5 = wave*2 + i/4; /2 = wave
-        else feat = row;
-        b_off[i] = (uint32_t)(n0 + feat) * (uint32_t)K * 2u + piece * 16;
+        const int row = i * 32 + (tid >> 3);
+        a_off[i] = (uint32_t)min(row, cnt - 1) * (uint32_t)K * 2u + (tid & 7) * 16;
     }
-    const int dma_off = wave * 8 * 1024;  // this wavefront's first row group, in bytes
-
-    // i < 4 of a gated tile are rows of W1 (gate), i >= 4 rows of W3 (up): row>>5 = 2*wave + i/4.
-    auto issue = [&](char* la, char* lb, int kt) {
+    // LDS position of piece i: row*128 + swizzled piece; (row >> 1) & 7 does not depend on i, so
+    // the eight positions are one register plus multiples of 4096
+    const int a_lds0 = (tid >> 3) * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
+    struct ATile {
+        u32x4 v[8];
+    };
+    auto load_a = [&](ATile& r, int kt) {
         const char* ab = a_base + (size_t)kt * (kBK * 2);
-        const char* bb0 = b_base0 + (size_t)kt * (kBK * 2);
-        const char* bb1 = b_base1 + (size_t)kt * (kBK * 2);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(ab + a_off[i]), (lptr_t)(la + dma_off + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)((i < 4 ? bb0 : bb1) + b_off[i]),
-                                             (lptr_t)(lb + dma_off + i * 1024), 16, 0, 0);
-        }
+        for (int i = 0; i < 8; ++i) r.v[i] = *reinterpret_cast<const u32x4*>(ab + a_off[i]);
+    };
+    auto store_a = [&](const ATile& r, int stage) {
+        char* base = lds_a + stage * kTileBytes;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(base + a_lds0 + i * 4096) = r.v[i];
     };
 
-    // ---- operand addressing ------------------------------------------------------------------
-    // fragment of 32 rows x 16 k: lane reads row (lane & 31), logical piece kk*2 + lane/32
-    const int lr = lane & 31;
+    // ---- weight operand: fragment-packed pool -> registers ------------------------------------------
+    // Wavefront w owns weight rows [64w, 64w+64) of the tile: two 32-row blocks.  For the gated
+    // product they are block (n0 + 32w)/32 of W1 (gate) and the same block of W3 (up), so that a
+    // lane holds matching gate and up values.  Fragment ks of a block is 1 KB at ks*1024.
+    const size_t frag_bytes_per_block = (size_t)(K / 16) * 1024;
+    const char* wb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint16_t* w = (MODE == kTModeSwigluH && i == 1) ? W1 : W0;
+        const int nb = MODE == kTModeSwigluH ? (n0 + wave * 32) / 32 : (n0 + wave * 64 + i * 32) / 32;
+        wb[i] = reinterpret_cast<const char*>(w) + ((size_t)s * (N / 32) + nb) * frag_bytes_per_block + lane * 16;
+    }
+
+    // ---- token fragments from LDS ------------------------------------------------------------------
+    // Slice kk (16 k) of a step: lane (row lane%32, half h = lane/32) reads logical piece 4h + kk,
+    // the 8 k values that the packed weight fragment pairs with it.
     int frag_off[4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) frag_off[kk] = lr * 128 + (((kk * 2 + (lane >> 5)) ^ ((lr >> 1) & 7)) << 4);
+    for (int kk = 0; kk < 4; ++kk) frag_off[kk] = lr * 128 + ((((lane >> 5) * 4 + kk) ^ ((lr >> 1) & 7)) << 4);
 
-    f32x16 acc[8][2];  // [token tile][weight-row tile]
+    f32x16 acc[8][2];  // [token tile][weight block]
 #pragma unroll
     for (int j = 0; j < 8; ++j)
 #pragma unroll
@@ -224,93 +227,115 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
             for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
 
     // Main loop, instantiated for NJ = number of 32-row token sub-tiles that hold rows (8 for
-    // every tile but the last one of a slot).  Stage 0 holds even k steps, stage 1 odd ones.
-    // While k step t is multiplied the DMA of step t+1 is in flight; operand fragments are
-    // fetched one 16-k slice ahead of the matrix instructions that use them; the barrier sits
-    // before the last slice so that the first fragments of the next step are fetched in its
-    // shadow.  The scheduling hints put one LDS read (and one DMA issue) in the shadow of each
-    // matrix instruction.
-    const int nkt = K / kBK;  // even: K is a multiple of 256
+    // every tile but the last one of a slot).
+    //
+    // Pipeline (k step t = 64 k = four 16-k slices; step t's tokens live in LDS stage t mod 3):
+    //   weights   slice g is loaded straight into registers 4 slices (one step) before use;
+    //   tokens    step t is loaded into registers during step t-5, written to its LDS stage during
+    //             step t-3 (right after the barrier that frees the stage), and read from step t-1's
+    //             last slice on; fragments are fetched one slice ahead of the matrix instructions;
+    //   barrier   one per step, before its last slice.
+    // Every load is an ordinary load, so the compiler inserts exact waits; the loop is unrolled by
+    // two steps so that the rings of registers are indexed statically.
+    const int nkt = K / kBK;         // even: K is a multiple of 256
     const int last = nkt - 1;
+    const int last_slice = K / 16 - 1;
     auto run = [&](auto njc) {
         constexpr int NJ = decltype(njc)::value;
-        constexpr int NR = 2 + NJ, NM = 2 * NJ;
-        struct Frags {
-            bf16x8 b[2], a[NJ];
+        constexpr int NM = 2 * NJ;
+        struct AFrags {
+            bf16x8 a[NJ];
         };
-        auto load_frags = [&](Frags& fr, const char* la, const char* lb, int kk) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                fr.b[i] = *reinterpret_cast<const bf16x8*>(lb + (wave * 64 + i * 32) * 128 + frag_off[kk]);
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                fr.a[j] = *reinterpret_cast<const bf16x8*>(la + j * 32 * 128 + frag_off[kk]);
+        struct BFrags {
+            u32x4 b[2];
         };
-        auto mma = [&](const Frags& fr) {
+        auto load_af = [&](AFrags& fr, int stage, int kk) {
+            const char* base = lds_a + stage * kTileBytes + frag_off[kk];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) fr.a[j] = *reinterpret_cast<const bf16x8*>(base + j * 32 * 128);
+        };
+        auto load_bf = [&](BFrags& fr, int g) {
+            const size_t o = (size_t)min(g, last_slice) * 1024;  // past the end: a harmless reload
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fr.b[i] = *reinterpret_cast<const u32x4*>(wb[i] + o);
+        };
+        auto mma = [&](const AFrags& fa, const BFrags& fb) {
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr.b[i], fr.a[j], acc[j][i], 0, 0, 0);
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb.b[i]), fa.a[j],
+                                                                        acc[j][i], 0, 0, 0);
         };
+        // scheduling hints: LDS reads, weight loads (and, in a step's last slice, the LDS writes
+        // and token loads) each in the shadow of one matrix instruction
         auto sched = [&]() {
 #pragma unroll
-            for (int q = 0; q < (NM > NR ? NM : NR); ++q) {
+            for (int q = 0; q < (NM > NJ ? NM : NJ); ++q) {
                 if (q < NM) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (q < NJ) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (q < 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
         };
-        auto sched_dma = [&]() {
+        auto sched_last = [&]() {
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
+            for (int q = 0; q < (NM > 10 ? NM : 10); ++q) {
                 if (q < NM) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (q < NR) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                if (q < 8) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                if (q < NJ) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (q < 10) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
         };
-        Frags f0, f1;
-        issue(lds_a0, lds_b0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-        __syncthreads();
-        issue(lds_a1, lds_b1, 1);
-        load_frags(f0, lds_a0, lds_b0, 0);
+
+        ATile ra[2];
+        BFrags bq[4];
+        AFrags f0, f1;
+        // prologue: steps 0..2 into the three stages, steps 3 and 4 on their way into registers
+        load_a(ra[0], 0);
+        load_a(ra[1], 1);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) load_bf(bq[g], g);
+        store_a(ra[0], 0);
+        load_a(ra[0], min(2, last));
+        store_a(ra[1], 1);
+        load_a(ra[1], min(3, last));
+        store_a(ra[0], 2);
+        load_a(ra[0], min(4, last));
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        load_af(f0, 0, 0);
+
+        int st = 0;  // LDS stage of step kt
         for (int kt = 0; kt < nkt; kt += 2) {
-            // k step kt from stage 0
-            load_frags(f1, lds_a0, lds_b0, 1);
-            mma(f0);
-            sched();
-            load_frags(f0, lds_a0, lds_b0, 2);
-            mma(f1);
-            sched();
-            load_frags(f1, lds_a0, lds_b0, 3);
-            mma(f0);
-            sched();
-            __builtin_amdgcn_s_waitcnt(0x0070);
-            __syncthreads();  // step kt+1 has landed in stage 1; nobody reads stage 0 any more
-            issue(lds_a0, lds_b0, min(kt + 2, last));  // past the end: a harmless reload of the last step
-            load_frags(f0, lds_a1, lds_b1, 0);
-            mma(f1);
-            sched_dma();
-            // k step kt+1 from stage 1
-            load_frags(f1, lds_a1, lds_b1, 1);
-            mma(f0);
-            sched();
-            load_frags(f0, lds_a1, lds_b1, 2);
-            mma(f1);
-            sched();
-            load_frags(f1, lds_a1, lds_b1, 3);
-            mma(f0);
-            sched();
-            __builtin_amdgcn_s_waitcnt(0x0070);
-            __syncthreads();  // step kt+2 has landed in stage 0; nobody reads stage 1 any more
-            issue(lds_a1, lds_b1, min(kt + 3, last));
-            load_frags(f0, lds_a0, lds_b0, 0);
-            mma(f1);
-            sched_dma();
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int t = kt + u;
+                const int stn = st == kStagesA - 1 ? 0 : st + 1;
+                const int g = 4 * t;
+                load_af(f1, st, 1);
+                mma(f0, bq[0]);
+                load_bf(bq[0], g + 4);
+                sched();
+                load_af(f0, st, 2);
+                mma(f1, bq[1]);
+                load_bf(bq[1], g + 5);
+                sched();
+                load_af(f1, st, 3);
+                mma(f0, bq[2]);
+                load_bf(bq[2], g + 6);
+                sched();
+                // all fragments of stage st are in registers; after the barrier the stage is free
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                store_a(ra[(u + 1) & 1], st);                  // step t+3
+                load_a(ra[(u + 1) & 1], min(t + 5, last));
+                load_af(f0, stn, 0);
+                mma(f1, bq[3]);
+                load_bf(bq[3], g + 7);
+                sched_last();
+                st = stn;
+            }
         }
-        __builtin_amdgcn_s_waitcnt(0x0070);  // drain the trailing reloads before the workgroup ends
     };
-    switch (min(8, (cnt - m0 + 31) / 32)) {
+    switch (min(8, (cnt + 31) / 32)) {
         case 8: run(std::integral_constant<int, 8>{}); break;
         case 7: run(std::integral_constant<int, 7>{}); break;
         case 6: run(std::integral_constant<int, 6>{}); break;

@@ -121,12 +121,32 @@ def test_validate_inputs(mm, gc):
     assert not mm.validate_inputs(case.shape, case.vid, badM, case.ws)
 
 
+def packed_layout_bf16(W):
+    """Plain [S, K, N] ("in x out") bf16 bit patterns -> the documented fragment layout, by the
+    index formula of include/mmoe.h (written with numpy index arithmetic, no kernel code)."""
+    S, K, N = W.shape
+    n = np.arange(N)[None, :]
+    k = np.arange(K)[:, None]
+    m, h, kk = k // 64, (k % 64) // 32, (k % 32) // 8
+    ks = 4 * m + kk
+    off = ((((n // 32) * (K // 16) + ks) * 64 + 32 * h + n % 32) * 8 + k % 8)        # [K, N], within a slot
+    out = np.empty((S, K * N), W.dtype)
+    for s in range(S):
+        out[s, off.reshape(-1)] = W[s].reshape(-1)
+    return out
+
+
 def test_pack_round_trip(mm, gc):
     cfg = synth.Config("pack", 4, 256, 512, 1, 3, 1, "bf16", "swiglu", seed=15)
     inp = synth.make_inputs(cfg)
     case = gc.DeviceCase(cfg, inp)
-    assert np.array_equal(gc.bits(case.W1p), inp["W1"].transpose(0, 2, 1))
-    assert np.array_equal(gc.bits(case.W3p), inp["W3"].transpose(0, 2, 1))
+    for packed, plain in ((case.W1p, inp["W1"]), (case.W3p, inp["W3"]), (case.W2p, inp["W2"])):
+        got = gc.bits(packed).reshape(plain.shape[0], -1)
+        assert np.array_equal(got, packed_layout_bf16(plain))
+    cfg = synth.Config("pack32", 4, 256, 512, 1, 2, 1, "f32", "relu", seed=16)
+    inp = synth.make_inputs(cfg)
+    case = gc.DeviceCase(cfg, inp)
+    assert np.array_equal(gc.bits(case.W1p), inp["W1"].transpose(0, 2, 1))      # fp32: the transpose
     assert np.array_equal(gc.bits(case.W2p), inp["W2"].transpose(0, 2, 1))
 
 
