@@ -230,11 +230,15 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
     // every tile but the last one of a slot).
     //
     // Pipeline (k step t = 64 k = four 16-k slices; step t's tokens live in LDS stage t mod 3):
-    //   weights   slice g is loaded straight into registers 4 slices (one step) before use;
-    //   tokens    step t is loaded into registers during step t-5, written to its LDS stage during
-    //             step t-3 (right after the barrier that frees the stage), and read from step t-1's
-    //             last slice on; fragments are fetched one slice ahead of the matrix instructions;
-    //   barrier   one per step, before its last slice.
+    //   weights   slice g is loaded straight into registers 8 slices (two steps) before use;
+    //   tokens    step t is loaded into registers during step t-5 and written to its LDS stage
+    //             during step t-3, so a load has two steps to arrive; token fragments roll
+    //             through one set of registers: as soon as the two matrix instructions that use
+    //             fragment j have been issued, fragment j of the next slice is fetched into it;
+    //   barrier   one per step, in the middle of its last slice: by then every wavefront's
+    //             reads of the step's stage have returned (only the first NJ/2 fetches of the
+    //             next stage may be in flight), so nobody waits for LDS, and the stage can take
+    //             the tokens of step t+3.
     // Every load is an ordinary load, so the compiler inserts exact waits; the loop is unrolled by
     // two steps so that the rings of registers are indexed statically.
     const int nkt = K / kBK;         // even: K is a multiple of 256
@@ -242,59 +246,45 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
     const int last_slice = K / 16 - 1;
     auto run = [&](auto njc) {
         constexpr int NJ = decltype(njc)::value;
-        constexpr int NM = 2 * NJ;
-        struct AFrags {
-            bf16x8 a[NJ];
-        };
+        constexpr int NH = NJ / 2;  // fetches of the next stage issued before the barrier
         struct BFrags {
             u32x4 b[2];
         };
-        auto load_af = [&](AFrags& fr, int stage, int kk) {
-            const char* base = lds_a + stage * kTileBytes + frag_off[kk];
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) fr.a[j] = *reinterpret_cast<const bf16x8*>(base + j * 32 * 128);
-        };
+        bf16x8 fa[NJ];
+        auto frag_ptr = [&](int stage, int kk) { return lds_a + stage * kTileBytes + frag_off[kk]; };
         auto load_bf = [&](BFrags& fr, int g) {
             const size_t o = (size_t)min(g, last_slice) * 1024;  // past the end: a harmless reload
 #pragma unroll
             for (int i = 0; i < 2; ++i) fr.b[i] = *reinterpret_cast<const u32x4*>(wb[i] + o);
         };
-        auto mma = [&](const AFrags& fa, const BFrags& fb) {
+        // one token sub-tile against both weight blocks, then its fragment of the next slice
+        auto mma_roll = [&](int j, const BFrags& fb, const char* next) {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb.b[i]), fa.a[j],
-                                                                        acc[j][i], 0, 0, 0);
+            for (int i = 0; i < 2; ++i)
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb.b[i]), fa[j],
+                                                                    acc[j][i], 0, 0, 0);
+            fa[j] = *reinterpret_cast<const bf16x8*>(next + j * 32 * 128);
         };
-        // scheduling hints: LDS reads, weight loads (and, in a step's last slice, the LDS writes
-        // and token loads) each in the shadow of one matrix instruction
-        auto sched = [&]() {
+        // a slice whose successor lies in the same LDS stage
+        auto slice = [&](BFrags& fb, const char* next, int g_reload) {
 #pragma unroll
-            for (int q = 0; q < (NM > NJ ? NM : NJ); ++q) {
-                if (q < NM) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (q < NJ) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if (q < 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
-        };
-        auto sched_last = [&]() {
+            for (int j = 0; j < NJ; ++j) mma_roll(j, fb, next);
+            load_bf(fb, g_reload);
 #pragma unroll
-            for (int q = 0; q < (NM > 10 ? NM : 10); ++q) {
-                if (q < NM) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (q < 8) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                if (q < NJ) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if (q < 10) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            for (int j = 0; j < NJ; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
+            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
         };
 
         ATile ra[2];
-        BFrags bq[4];
-        AFrags f0, f1;
+        BFrags bq[8];
         // prologue: steps 0..2 into the three stages, steps 3 and 4 on their way into registers
         load_a(ra[0], 0);
         load_a(ra[1], 1);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) load_bf(bq[g], g);
+        for (int g = 0; g < 8; ++g) load_bf(bq[g], g);
         store_a(ra[0], 0);
         load_a(ra[0], min(2, last));
         store_a(ra[1], 1);
@@ -302,7 +292,11 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
         store_a(ra[0], 2);
         load_a(ra[0], min(4, last));
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        load_af(f0, 0, 0);
+        {
+            const char* p0 = frag_ptr(0, 0);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) fa[j] = *reinterpret_cast<const bf16x8*>(p0 + j * 32 * 128);
+        }
 
         int st = 0;  // LDS stage of step kt
         for (int kt = 0; kt < nkt; kt += 2) {
@@ -311,26 +305,39 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
                 const int t = kt + u;
                 const int stn = st == kStagesA - 1 ? 0 : st + 1;
                 const int g = 4 * t;
-                load_af(f1, st, 1);
-                mma(f0, bq[0]);
-                load_bf(bq[0], g + 4);
-                sched();
-                load_af(f0, st, 2);
-                mma(f1, bq[1]);
-                load_bf(bq[1], g + 5);
-                sched();
-                load_af(f1, st, 3);
-                mma(f0, bq[2]);
-                load_bf(bq[2], g + 6);
-                sched();
-                // all fragments of stage st are in registers; after the barrier the stage is free
-                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-                store_a(ra[(u + 1) & 1], st);                  // step t+3
-                load_a(ra[(u + 1) & 1], min(t + 5, last));
-                load_af(f0, stn, 0);
-                mma(f1, bq[3]);
-                load_bf(bq[3], g + 7);
-                sched_last();
+                slice(bq[4 * u + 0], frag_ptr(st, 1), g + 8);
+                slice(bq[4 * u + 1], frag_ptr(st, 2), g + 9);
+                slice(bq[4 * u + 2], frag_ptr(st, 3), g + 10);
+                // last slice of the step: its fragments are in flight or in registers
+                {
+                    BFrags& fb = bq[4 * u + 3];
+                    const char* next = frag_ptr(stn, 0);
+#pragma unroll
+                    for (int j = 0; j < NH; ++j) mma_roll(j, fb, next);
+#pragma unroll
+                    for (int j = 0; j < NH; ++j) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    // all reads of stage st have returned except, possibly, the NH fetches just issued,
+                    // which read the next stage
+                    asm volatile("s_waitcnt lgkmcnt(%0)\n\ts_barrier" ::"n"(NH) : "memory");
+                    store_a(ra[(u + 1) & 1], st);  // tokens of step t+3
+                    load_a(ra[(u + 1) & 1], min(t + 5, last));
+#pragma unroll
+                    for (int j = NH; j < NJ; ++j) mma_roll(j, fb, next);
+                    load_bf(fb, g + 11);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        if (q < NJ - NH) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        }
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+                }
                 st = stn;
             }
         }
