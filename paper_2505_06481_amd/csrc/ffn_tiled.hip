@@ -37,7 +37,10 @@ enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2 };
 constexpr int kBM = 256;  // token rows per tile
 constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
-constexpr int kTThreads = 256;
+#ifndef MMOE_TILED_NB
+#define MMOE_TILED_NB 2
+#endif
+constexpr int kTiledNB = MMOE_TILED_NB;  // weight blocks per wavefront: 1 = eight wavefronts, 2 = four
 constexpr int kXcds = 8;
 constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB: one step of the token operand
 constexpr int kStagesA = 3;
@@ -137,8 +140,11 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
     }
 }
 
-template <int MODE>
-__global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __restrict__ A,
+// NB = 32-row weight blocks per wavefront: 2 -> four wavefronts (one per SIMD), 1 -> eight
+// wavefronts (two per SIMD, so that one can issue matrix instructions while the other is
+// busy issuing loads).
+template <int MODE, int NB>
+__global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __restrict__ A,
                                                              const int32_t* __restrict__ tab, int list_hi,
                                                              int list_lo, const uint16_t* __restrict__ W0,
                                                              const uint16_t* __restrict__ W1,
@@ -165,49 +171,62 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
     constexpr int kFeat = MODE == kTModeSwigluH ? kBN / 2 : kBN;  // output features per tile
     const int n0 = nt * kFeat;
 
+    constexpr int kWaves = 8 / NB;
+    constexpr int kThreads = kWaves * 64;
+    constexpr int kNP = 2048 / kThreads;  // 16-byte pieces of a token tile per thread
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps bases in scalar registers
     const int lr = lane & 31;
 
     // ---- token operand: global -> registers -> LDS ----------------------------------------------
-    // Piece id = i*256 + tid (i < 8) of a [256 rows][8 pieces of 16 bytes] tile: 8 consecutive
-    // threads read one row's 128 contiguous bytes.  Rows past the end of the group re-read its
-    // last row (they are multiplied but never stored).
+    // Piece id = i*kThreads + tid (i < kNP) of a [256 rows][8 pieces of 16 bytes] tile: 8
+    // consecutive threads read one row's 128 contiguous bytes.  Rows past the end of the group
+    // re-read its last row (they are multiplied but never stored).
     const char* a_base = reinterpret_cast<const char*>(A) + (size_t)r0 * K * 2;
-    uint32_t a_off[8];
+    uint32_t a_off[kNP];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int row = i * 32 + (tid >> 3);
+    for (int i = 0; i < kNP; ++i) {
+        const int row = i * (kThreads / 8) + (tid >> 3);
         a_off[i] = (uint32_t)min(row, cnt - 1) * (uint32_t)K * 2u + (tid & 7) * 16;
     }
     // LDS position of piece i: row*128 + swizzled piece; (row >> 1) & 7 does not depend on i, so
-    // the eight positions are one register plus multiples of 4096
+    // the positions are one register plus multiples of kThreads*16
     const int a_lds0 = (tid >> 3) * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
     struct ATile {
-        u32x4 v[8];
+        u32x4 v[kNP];
     };
     auto load_a = [&](ATile& r, int kt) {
         const char* ab = a_base + (size_t)kt * (kBK * 2);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) r.v[i] = *reinterpret_cast<const u32x4*>(ab + a_off[i]);
+        for (int i = 0; i < kNP; ++i) r.v[i] = *reinterpret_cast<const u32x4*>(ab + a_off[i]);
     };
     auto store_a = [&](const ATile& r, int stage) {
         char* base = lds_a + stage * kTileBytes;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(base + a_lds0 + i * 4096) = r.v[i];
+        for (int i = 0; i < kNP; ++i) *reinterpret_cast<u32x4*>(base + a_lds0 + i * (kThreads * 16)) = r.v[i];
     };
 
     // ---- weight operand: fragment-packed pool -> registers ------------------------------------------
-    // Wavefront w owns weight rows [64w, 64w+64) of the tile: two 32-row blocks.  For the gated
-    // product they are block (n0 + 32w)/32 of W1 (gate) and the same block of W3 (up), so that a
-    // lane holds matching gate and up values.  Fragment ks of a block is 1 KB at ks*1024.
+    // NB = 2: wavefront w owns weight rows [64w, 64w+64) of the tile, two 32-row blocks; for the
+    // gated product they are block (n0 + 32w)/32 of W1 (gate) and the same block of W3 (up), so
+    // that a lane holds matching gate and up values.  NB = 1: wavefront w owns one block; for the
+    // gated product wavefronts 2p and 2p+1 hold the gate and the up values of features
+    // [n0 + 32p, n0 + 32p + 32) and meet in the epilogue.  Fragment ks of a block is 1 KB at ks*1024.
     const size_t frag_bytes_per_block = (size_t)(K / 16) * 1024;
-    const char* wb[2];
+    const int fgrp = NB == 2 ? wave : (wave >> 1);      // gated: 32-feature group of this wavefront
+    const bool up_role = NB == 1 && (wave & 1);         // gated, NB = 1: this wavefront multiplies W3
+    const char* wb[NB];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const uint16_t* w = (MODE == kTModeSwigluH && i == 1) ? W1 : W0;
-        const int nb = MODE == kTModeSwigluH ? (n0 + wave * 32) / 32 : (n0 + wave * 64 + i * 32) / 32;
+    for (int i = 0; i < NB; ++i) {
+        const uint16_t* w = W0;
+        int nb;
+        if (MODE == kTModeSwigluH) {
+            if (NB == 2 ? i == 1 : up_role) w = W1;
+            nb = (n0 + fgrp * 32) / 32;
+        } else {
+            nb = (n0 + wave * (32 * NB) + i * 32) / 32;
+        }
         wb[i] = reinterpret_cast<const char*>(w) + ((size_t)s * (N / 32) + nb) * frag_bytes_per_block + lane * 16;
     }
 
@@ -218,11 +237,11 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) frag_off[kk] = lr * 128 + ((((lane >> 5) * 4 + kk) ^ ((lr >> 1) & 7)) << 4);
 
-    f32x16 acc[8][2];  // [token tile][weight block]
+    f32x16 acc[8][NB];  // [token tile][weight block]
 #pragma unroll
     for (int j = 0; j < 8; ++j)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NB; ++i)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
 
@@ -248,19 +267,19 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
         constexpr int NJ = decltype(njc)::value;
         constexpr int NH = NJ / 2;  // fetches of the next stage issued before the barrier
         struct BFrags {
-            u32x4 b[2];
+            u32x4 b[NB];
         };
         bf16x8 fa[NJ];
         auto frag_ptr = [&](int stage, int kk) { return lds_a + stage * kTileBytes + frag_off[kk]; };
         auto load_bf = [&](BFrags& fr, int g) {
             const size_t o = (size_t)min(g, last_slice) * 1024;  // past the end: a harmless reload
 #pragma unroll
-            for (int i = 0; i < 2; ++i) fr.b[i] = *reinterpret_cast<const u32x4*>(wb[i] + o);
+            for (int i = 0; i < NB; ++i) fr.b[i] = *reinterpret_cast<const u32x4*>(wb[i] + o);
         };
         // one token sub-tile against both weight blocks, then its fragment of the next slice
         auto mma_roll = [&](int j, const BFrags& fb, const char* next) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < NB; ++i)
                 acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb.b[i]), fa[j],
                                                                     acc[j][i], 0, 0, 0);
             fa[j] = *reinterpret_cast<const bf16x8*>(next + j * 32 * 128);
@@ -272,10 +291,10 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
             load_bf(fb, g_reload);
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, NB, 0);
         };
 
         ATile ra[2];
@@ -316,7 +335,7 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
                     for (int j = 0; j < NH; ++j) mma_roll(j, fb, next);
 #pragma unroll
                     for (int j = 0; j < NH; ++j) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
                         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     }
                     // all reads of stage st have returned except, possibly, the NH fetches just issued,
@@ -328,15 +347,17 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
                     for (int j = NH; j < NJ; ++j) mma_roll(j, fb, next);
                     load_bf(fb, g + 11);
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) {
+                    for (int q = 0; q < (kNP > NJ - NH ? kNP : NJ - NH); ++q) {
                         if (q < NJ - NH) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
                             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                         }
-                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                        if (q < kNP) {
+                            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                        }
                     }
-                    __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, NB, 0);
                 }
                 st = stn;
             }
@@ -364,43 +385,86 @@ __global__ __launch_bounds__(kTThreads, 1) void tiled_kernel(const uint16_t* __r
     constexpr int kPitch = kRowB + 16;                // padded: conflict-free 16-byte column writes
     constexpr int kLpr = kRowB / 16;                  // lanes that read one row back
     constexpr int kRpi = 64 / kLpr;                   // rows per read-back instruction
-    constexpr int kChunks = MODE == kTModeSwigluH ? 1 : 2;  // 32-feature chunks per wavefront
-    __shared__ __attribute__((aligned(16))) char lds_epi[4][32 * (32 * 4 + 16)];
+    constexpr int kChunks = MODE == kTModeSwigluH ? 1 : NB;       // 32-feature chunks this wavefront stores
+    constexpr bool kPaired = MODE == kTModeSwigluH && NB == 1;    // gate and up live in two wavefronts
+    const int wfeat = MODE == kTModeSwigluH ? fgrp * 32 : wave * (32 * NB);
+    __shared__ __attribute__((aligned(16))) char lds_epi[kWaves][32 * (32 * 4 + 16)];
     char* ebuf = lds_epi[wave];
-    char* const obase = reinterpret_cast<char*>(out) +
-                        ((size_t)r0 * N + n0 + wave * (32 * kChunks)) * kEsz + (size_t)(lane / kLpr) * N * kEsz +
-                        (lane % kLpr) * 16;
+    char* const obase = reinterpret_cast<char*>(out) + ((size_t)r0 * N + n0 + wfeat) * kEsz +
+                        (size_t)(lane / kLpr) * N * kEsz + (lane % kLpr) * 16;
+    // o[4q + e]: the 16 finished values of this lane for token sub-tile j, feature chunk c
+    auto emit = [&](int j, int c, const float (&o)[16]) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        if (j * 32 >= cnt) break;  // uniform
+        for (int q = 0; q < 4; ++q) {
+            char* at = ebuf + lr * kPitch + (8 * q + 4 * (lane >> 5)) * kEsz;
+            if (kEsz == 4) {
+                *reinterpret_cast<f32x4*>(at) = f32x4{o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]};
+            } else {
+                u32x2 pk;
+                pk[0] = (uint32_t)f32_to_bf16_bits(o[4 * q]) | ((uint32_t)f32_to_bf16_bits(o[4 * q + 1]) << 16);
+                pk[1] = (uint32_t)f32_to_bf16_bits(o[4 * q + 2]) | ((uint32_t)f32_to_bf16_bits(o[4 * q + 3]) << 16);
+                *reinterpret_cast<u32x2*>(at) = pk;
+            }
+        }
 #pragma unroll
-        for (int c = 0; c < kChunks; ++c) {
+        for (int it = 0; it < 32 / kRpi; ++it) {
+            const int row = it * kRpi + lane / kLpr;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(ebuf + row * kPitch + (lane % kLpr) * 16);
+            if (j * 32 + row < cnt)
+                *reinterpret_cast<u32x4*>(obase + ((size_t)(j * 32 + it * kRpi) * N + c * 32) * kEsz) = v;
+        }
+    };
+    if (!kPaired) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float o[4];
+        for (int j = 0; j < 8; ++j) {
+            if (j * 32 >= cnt) break;  // uniform
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (MODE == kTModeSwigluH) o[e] = silu_mul_t(acc[j][0][4 * q + e], acc[j][1][4 * q + e]);
-                    else if (MODE == kTModeReluH) o[e] = fmaxf(acc[j][c][4 * q + e], 0.0f);
-                    else o[e] = acc[j][c][4 * q + e];
+            for (int c = 0; c < kChunks; ++c) {
+                float o[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    if (MODE == kTModeSwigluH) o[e] = silu_mul_t(acc[j][0][e], acc[j][NB - 1][e]);
+                    else if (MODE == kTModeReluH) o[e] = fmaxf(acc[j][c][e], 0.0f);
+                    else o[e] = acc[j][c][e];
                 }
-                char* at = ebuf + lr * kPitch + (8 * q + 4 * (lane >> 5)) * kEsz;
-                if (kEsz == 4) {
-                    *reinterpret_cast<f32x4*>(at) = f32x4{o[0], o[1], o[2], o[3]};
-                } else {
-                    u32x2 pk;
-                    pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
-                    pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
-                    *reinterpret_cast<u32x2*>(at) = pk;
+                emit(j, c, o);
+            }
+        }
+    } else {
+        // The up wavefront hands its accumulators to the gate wavefront of the same 32 features
+        // through the token stages, which nobody reads any more: four token sub-tiles per round,
+        // 4 KB per sub-tile, in accumulator order (so both sides use the same lane mapping).
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            if (r * 128 >= cnt) break;  // uniform over the workgroup
+            char* xb = lds_a + (size_t)fgrp * (4 * 4096) + lane * 16;
+            if (up_role) {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<f32x4*>(xb + (jj * 4 + q) * 1024) =
+                            f32x4{acc[4 * r + jj][0][4 * q], acc[4 * r + jj][0][4 * q + 1], acc[4 * r + jj][0][4 * q + 2],
+                                  acc[4 * r + jj][0][4 * q + 3]};
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            if (!up_role) {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int j = 4 * r + jj;
+                    if (j * 32 >= cnt) break;
+                    float o[16];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x4 u = *reinterpret_cast<const f32x4*>(xb + (jj * 4 + q) * 1024);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[4 * q + e] = silu_mul_t(acc[j][0][4 * q + e], u[e]);
+                    }
+                    emit(j, 0, o);
                 }
             }
-#pragma unroll
-            for (int it = 0; it < 32 / kRpi; ++it) {
-                const int row = it * kRpi + lane / kLpr;
-                const u32x4 v = *reinterpret_cast<const u32x4*>(ebuf + row * kPitch + (lane % kLpr) * 16);
-                if (j * 32 + row < cnt)
-                    *reinterpret_cast<u32x4*>(obase + ((size_t)(j * 32 + it * kRpi) * N + c * 32) * kEsz) = v;
-            }
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         }
     }
 }
@@ -428,18 +492,21 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets
     int nt_up, nt_down;
     tiled_nts(s, nt_up, nt_down);
     const TileLists L = tile_lists(P, s.S, nt_up, nt_down);
-    dim3 block(kTThreads);
+    dim3 block(512 / kTiledNB);
     const uint16_t* nul = nullptr;
     hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, L);
     if (s.act == MMOE_SWIGLU)
-        hipLaunchKernelGGL(tiled_kernel<kTModeSwigluH>, dim3(L.cap[0] * kXcds), block, 0, st, (const uint16_t*)Xg, tab,
-                           L.list[0][0], L.list[0][1], (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, nt_up);
+        hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH, kTiledNB>), dim3(L.cap[0] * kXcds), block, 0, st,
+                           (const uint16_t*)Xg, tab, L.list[0][0], L.list[0][1], (const uint16_t*)W1p,
+                           (const uint16_t*)W3p, H, d, f, nt_up);
     else
-        hipLaunchKernelGGL(tiled_kernel<kTModeReluH>, dim3(L.cap[0] * kXcds), block, 0, st, (const uint16_t*)Xg, tab,
-                           L.list[0][0], L.list[0][1], (const uint16_t*)W1p, nul, H, d, f, nt_up);
+        hipLaunchKernelGGL((tiled_kernel<kTModeReluH, kTiledNB>), dim3(L.cap[0] * kXcds), block, 0, st,
+                           (const uint16_t*)Xg, tab, L.list[0][0], L.list[0][1], (const uint16_t*)W1p, nul, H, d, f,
+                           nt_up);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    hipLaunchKernelGGL(tiled_kernel<kTModePlainF32>, dim3(L.cap[1] * kXcds), block, 0, st, (const uint16_t*)H, tab,
-                       L.list[1][0], L.list[1][1], (const uint16_t*)W2p, nul, (void*)Yg, f, d, nt_down);
+    hipLaunchKernelGGL((tiled_kernel<kTModePlainF32, kTiledNB>), dim3(L.cap[1] * kXcds), block, 0, st,
+                       (const uint16_t*)H, tab, L.list[1][0], L.list[1][1], (const uint16_t*)W2p, nul, (void*)Yg, f, d,
+                       nt_down);
     return launch_status();
 }
 
