@@ -138,6 +138,96 @@ __global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_
     }
 }
 
+// The three kernels above in one, for batches whose pairs fit one workgroup's chunk (decode):
+// same ranks, same results, two launches fewer.
+__global__ __launch_bounds__(kPermThreads) void slot_group_small_kernel(
+    const int32_t* __restrict__ vid, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ M,
+    int32_t* __restrict__ slot, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm, int P, int k, int V, int E, int S)
+{
+    __shared__ int wtot[kPermWaves][kMaxS];
+    __shared__ int cursor[kPermWaves][kMaxS];
+    __shared__ int tot[kMaxS];
+    __shared__ int myslot[kPermChunk];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    for (int i = threadIdx.x; i < kPermWaves * S; i += kPermThreads) wtot[i / S][i % S] = 0;
+    __syncthreads();
+    const int wbase = wave * kPairsPerWave;
+    for (int i = lane; i < kPairsPerWave; i += kWave) {
+        int p = wbase + i;
+        if (p < P) {
+            int v = min(max(vid[p / k], 0), V - 1);
+            int e = min(max(topk_idx[p], 0), E - 1);
+            int s = min(max(M[v * E + e], 0), S - 1);
+            slot[p] = s;
+            myslot[p] = s;
+            atomicAdd(&wtot[wave][s], 1);
+        }
+    }
+    __syncthreads();
+    for (int s = threadIdx.x; s < S; s += kPermThreads) {
+        int run = 0;
+#pragma unroll
+        for (int w = 0; w < kPermWaves; ++w) run += wtot[w][s];
+        tot[s] = run;
+        counts[s] = run;
+    }
+    __syncthreads();
+    if (threadIdx.x < kWave) {  // exclusive scan of the S totals, 64 at a time; tot[s] becomes offsets[s]
+        int carry = 0;
+        for (int s0 = 0; s0 < S; s0 += kWave) {
+            int s = s0 + threadIdx.x;
+            int c = s < S ? tot[s] : 0;
+            int incl = c;
+#pragma unroll
+            for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+                int o = __shfl_up(incl, dlt, kWave);
+                if ((int)threadIdx.x >= dlt) incl += o;
+            }
+            if (s < S) {
+                tot[s] = carry + incl - c;
+                offsets[s] = carry + incl - c;
+            }
+            carry += __shfl(incl, kWave - 1, kWave);
+        }
+        if (threadIdx.x == 0) offsets[S] = carry;
+    }
+    __syncthreads();
+    for (int s = threadIdx.x; s < S; s += kPermThreads) {
+        int run = tot[s];
+#pragma unroll
+        for (int w = 0; w < kPermWaves; ++w) {
+            cursor[w][s] = run;
+            run += wtot[w][s];
+        }
+    }
+    __syncthreads();
+    volatile int* cur = cursor[wave];
+    for (int i0 = 0; i0 < kPairsPerWave; i0 += kWave) {
+        int p = wbase + i0 + lane;
+        bool valid = p < P;
+        if (!__ballot(valid)) break;  // uniform over the wavefront
+        int s = valid ? myslot[p] : -1;
+        unsigned long long todo = __ballot(valid);
+        while (todo) {
+            int leader = __ffsll((long long)todo) - 1;
+            int s0 = __shfl(s, leader, kWave);
+            unsigned long long m = __ballot(valid && s == s0);
+            if (valid && s == s0) {
+                int rank = __popcll(m & ((1ull << lane) - 1ull));
+                int r = cur[s0] + rank;
+                perm[r] = p;
+                inv_perm[p] = r;
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane == leader) cur[s0] = cur[s0] + __popcll(m);
+            __builtin_amdgcn_wave_barrier();
+            todo &= ~m;
+        }
+    }
+}
+
 // Xg[r,:] = X[perm[r] / k, :], one wavefront per row, 16 bytes per lane per step.
 __global__ __launch_bounds__(kPermThreads) void gather_rows_kernel(const u32x4* __restrict__ X,
                                                                    const int32_t* __restrict__ perm,
@@ -179,12 +269,17 @@ int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const
                    int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk, hipStream_t st)
 {
     const int P = s.T * s.top_k;
+    if (nblk == 1)
+        hipLaunchKernelGGL(slot_group_small_kernel, dim3(1), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot, counts,
+                           offsets, perm, inv_perm, P, s.top_k, s.V, s.E, s.S);
+    else {
     hipLaunchKernelGGL(slot_hist_kernel, dim3(nblk), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot,
                        blk_counts, P, s.top_k, s.V, s.E, s.S);
     hipLaunchKernelGGL(slot_scan_kernel, dim3(1), dim3(kPermThreads), 0, st, blk_counts, blk_base, counts,
                        offsets, nblk, s.S);
     hipLaunchKernelGGL(slot_scatter_kernel, dim3(nblk), dim3(kPermThreads), 0, st, slot, blk_base, perm,
                        inv_perm, P, s.S);
+    }
     const int row_vec = (int)((size_t)s.d_model * elem_size(s.dtype) / 16);
     hipLaunchKernelGGL(gather_rows_kernel, dim3((P + kPermWaves - 1) / kPermWaves), dim3(kPermThreads), 0, st,
                        (const u32x4*)X, perm, (u32x4*)Xg, P, s.top_k, row_vec);

@@ -1,5 +1,5 @@
 // Step R: per-variant gate, top-k selection and coefficients (Algorithm 2, "gate(act)";
-// section 3.2).  One wavefront scores one token.
+// section 3.2).  One workgroup scores one token, its wavefronts share out the experts.
 //
 // The logit is an fp32 sum in the fixed order the header states: lane l owns the
 // elements i with (i div 4) mod 64 == l, which is exactly what a coalesced 4-element
@@ -14,8 +14,7 @@
 
 namespace mmoe {
 
-constexpr int kRouteWaves = 4;   // tokens per workgroup
-constexpr int kEC = 8;           // experts scored per sweep over the token
+constexpr int kRouteWaves = 8;   // wavefronts per token: they share out the experts
 
 template <typename T> struct Vec4;
 template <> struct Vec4<float> {
@@ -36,56 +35,56 @@ template <> struct Vec4<uint16_t> {
     }
 };
 
+// One workgroup per token; wavefront w scores experts w, w+8, ...  A token's dot product
+// with one expert is never split between wavefronts, so the summation order is the
+// contract's whatever the launch shape.  Four vectors per lane are fetched at a time to
+// keep eight loads in flight.
 template <typename T>
 __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     const T* __restrict__ X, const int32_t* __restrict__ vid, const T* __restrict__ Wr,
     const float* __restrict__ br, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d,
     int V, int E, int k)
 {
-    __shared__ float lds_logit[kRouteWaves][kMaxE];
+    __shared__ float lds_logit[kMaxE];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int t = blockIdx.x * kRouteWaves + wave;
-    if (t >= Tn) return;  // whole wavefront leaves; no workgroup barrier below
+    const int t = blockIdx.x;
 
     const int v = min(max(vid[t], 0), V - 1);  // out-of-range ids are the caller's error; stay in bounds
     const T* x = X + (size_t)t * d;
-    const T* wv = Wr + (size_t)v * E * d;
-    const int nvec = d / 4;  // d is a multiple of 256
+    const int nvec = d / 4;  // a multiple of 64: d is a multiple of 256
 
-    for (int e0 = 0; e0 < E; e0 += kEC) {
-        float acc[kEC];
+    for (int e = wave; e < E; e += kRouteWaves) {
+        const T* w = Wr + ((size_t)v * E + e) * d;
+        float acc = 0.0f;
+        int q = lane;
+        for (; q + 3 * kWave < nvec; q += 4 * kWave) {  // ascending i within the lane
+            float xv[4][4], wv[4][4];
 #pragma unroll
-        for (int c = 0; c < kEC; ++c) acc[c] = 0.0f;
-        for (int q = lane; q < nvec; q += kWave) {  // ascending i within the lane
-            float xv[4];
+            for (int u = 0; u < 4; ++u) {
+                Vec4<T>::load(x + 4 * (q + u * kWave), xv[u]);
+                Vec4<T>::load(w + 4 * (q + u * kWave), wv[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc = __builtin_fmaf(xv[u][c], wv[u][c], acc);
+        }
+        for (; q < nvec; q += kWave) {
+            float xv[4], wv[4];
             Vec4<T>::load(x + 4 * q, xv);
+            Vec4<T>::load(w + 4 * q, wv);
 #pragma unroll
-            for (int c = 0; c < kEC; ++c) {
-                if (e0 + c < E) {
-                    float wvv[4];
-                    Vec4<T>::load(wv + (size_t)(e0 + c) * d + 4 * q, wvv);
-                    acc[c] = __builtin_fmaf(xv[0], wvv[0], acc[c]);
-                    acc[c] = __builtin_fmaf(xv[1], wvv[1], acc[c]);
-                    acc[c] = __builtin_fmaf(xv[2], wvv[2], acc[c]);
-                    acc[c] = __builtin_fmaf(xv[3], wvv[3], acc[c]);
-                }
-            }
+            for (int c = 0; c < 4; ++c) acc = __builtin_fmaf(xv[c], wv[c], acc);
         }
+        float p = acc;
 #pragma unroll
-        for (int c = 0; c < kEC; ++c) {
-            float p = acc[c];
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) p = p + __shfl_xor(p, off, kWave);
-            if (e0 + c < E) {
-                if (br) p = p + br[(size_t)v * E + e0 + c];
-                if (lane == 0) lds_logit[wave][e0 + c] = p;
-            }
-        }
+        for (int off = 32; off >= 1; off >>= 1) p = p + __shfl_xor(p, off, kWave);
+        if (br) p = p + br[(size_t)v * E + e];
+        if (lane == 0) lds_logit[e] = p;
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __syncthreads();
+    if (wave != 0) return;
 
     // each lane looks after experts lane, lane+64, lane+128, lane+192
     constexpr int kPerLane = kMaxE / kWave;
@@ -93,7 +92,7 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
 #pragma unroll
     for (int q = 0; q < kPerLane; ++q) {
         int e = lane + q * kWave;
-        mine[q] = e < E ? lds_logit[wave][e] : -INFINITY;
+        mine[q] = e < E ? lds_logit[e] : -INFINITY;
     }
     uint32_t taken = 0;
     float sel[kMaxTopK];
@@ -145,7 +144,7 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
 int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const void* Wr, const float* br,
                  int32_t* topk_idx, float* topk_w, hipStream_t st)
 {
-    dim3 grid((s.T + kRouteWaves - 1) / kRouteWaves), block(kRouteWaves * kWave);
+    dim3 grid(s.T), block(kRouteWaves * kWave);
     if (s.dtype == MMOE_BF16)
         hipLaunchKernelGGL(route_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)X, vid,
                            (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k);
