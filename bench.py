@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-shaped companion run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = 96 tokens per oracle thread")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference point for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -130,7 +132,7 @@ def roofline(cfg, res, skinny):
         alg_bytes = active * nw * d * f * es + P * d * es + P * f * es
         ach = alg_bytes / dur_s / 1e9
         return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
-                    traffic=None, kernel="skinny_kernel (up product)", bytes_per_launch=alg_bytes,
+                    traffic=None, kernel=("skinny_frag_kernel" if cfg.dtype == "bf16" else "skinny_kernel") + " (up product)", bytes_per_launch=alg_bytes,
                     avg_launch_ms=dur_s * 1e3)
     flops = 2.0 * P * d * f * nw
     ach = flops / dur_s / 1e12
@@ -231,6 +233,15 @@ def main():
             "stages_ms": dres["stages_ms"],
             "roofline": roofline(dcfg, dres, True),
         }
+
+    if a.copy_calibration:
+        # a plain elementwise copy of known size: reads 1 GiB, writes 1 GiB per launch
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp, a.cpu_sample_tokens)

@@ -12,20 +12,19 @@
 // the 32-row matrix-core operand and tokens the 32-column one, hence a lane owns, for one
 // token, groups of 4 consecutive output features and stores 8 or 16 bytes at a time.
 //
-// Memory pipeline: global -> LDS copies are issued by the DMA path (global_load_lds, 16
-// bytes per lane, no staging registers) into a double-buffered pair of LDS tiles; the
-// copies of step kt+1 are in flight while step kt is multiplied; one barrier per step.
-// LDS tiles are [row][64 k] bf16 (128 bytes a row) with the 16-byte pieces xor-swizzled by
-// (row >> 1) & 7: the DMA writes a wavefront's 64 pieces to consecutive LDS addresses, so
-// the swizzle is applied on the global side (which piece a lane fetches).
+// Memory pipeline: the pool is stored as matrix-core fragments, so a wavefront loads its
+// weight operands straight from global memory into registers (16 bytes per lane, 1 KB per
+// instruction, contiguous), two steps ahead of their use.  Token rows go global -> registers
+// -> a three-stage ring of LDS tiles, [row][64 k] bf16 (128 bytes a row) with the 16-byte
+// pieces xor-swizzled by (row >> 1) & 7, and are read back as fragments; one barrier per step.
 //
 // Ragged groups: row ranges come from the device array `offsets`.  A one-workgroup
-// preparation kernel turns them into a table of row tiles; the product kernels map their
-// workgroup id to (slot, row tile, feature tile) through that table, so the host never
+// preparation kernel turns them into lists of tiles; the product kernels map their
+// workgroup id to (slot, row tile, feature tile) through those lists, so the host never
 // waits for the histogram.  Workgroup ids are dealt round-robin to the 8 XCDs by the
-// hardware; the id -> tile map gives XCD x the feature tiles nt with nt mod 8 == x, ordered
-// (slot, feature tile, row tile), so the workgroups resident on one XCD share weight and
-// activation panels in that XCD's L2 and every XCD sees the same mix of row tiles.
+// hardware; the id -> tile map gives XCD x the feature tiles nt with nt mod 8 == x, so the
+// workgroups resident on one XCD share weight and activation panels in that XCD's L2 and
+// every XCD sees the same mix of row tiles.
 #include <type_traits>
 
 #include "mmoe_internal.h"
@@ -44,6 +43,7 @@ constexpr int kTiledNB = MMOE_TILED_NB;  // weight blocks per wavefront: 1 = eig
 constexpr int kXcds = 8;
 constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB: one step of the token operand
 constexpr int kStagesA = 3;
+constexpr int kLongestFirstBelow = 8 * 256;  // tiles of a product: below this, partial tiles go last
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -61,8 +61,13 @@ __device__ __forceinline__ float silu_mul_t(float g, float u)
 //   four lists of int4 entries  {slot, feature tile within the XCD, first row, rows valid},
 //   one per (product, feature tiles per XCD): a product with NT feature tiles gives XCD x
 //   the tiles nt with nt mod 8 == x, that is ceil or floor of NT/8 of them; list entry
-//   `local` is the tile that the workgroup with id 8*local + x computes, in the order
-//   (slot, feature tile, row tile), row tile fastest.
+//   `local` is the tile that the workgroup with id 8*local + x computes.  A product with many
+//   tiles per compute unit lists them in the order (slot, feature tile, row tile), row tile
+//   fastest.  Workgroups start in id order as compute units become free, so a product with
+//   few tiles per compute unit (fewer than kLongestFirstBelow tiles in all) lists the longest
+//   work first: every full 256-row tile in that order, and after them the partial last tiles
+//   of the slots, those with the most rows first, so that the short ones fill the end of the
+//   launch.
 struct TileLists {
     int hdr;        // int32 index of tab[0]
     int list[2][2]; // [product: up, down][0: ceil(NT/8) per XCD, 1: floor] -> int4 index into tab
@@ -91,50 +96,80 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
                                                          int32_t* __restrict__ tab, int S, int nt_up, int nt_down,
                                                          TileLists L)
 {
-    __shared__ int part[256];
-    __shared__ int base[kMaxS + 1];  // first row tile of each slot
-    // thread t covers slots [t*per, (t+1)*per)
-    const int per = (S + 255) / 256;
-    const int s_lo = min((int)threadIdx.x * per, S), s_hi = min(s_lo + per, S);
-    int sum = 0;
-    for (int s = s_lo; s < s_hi; ++s) sum += (offsets[s + 1] - offsets[s] + kBM - 1) / kBM;
-    part[threadIdx.x] = sum;
+    __shared__ int cnt_s[kMaxS];       // rows of each slot
+    __shared__ int base[kMaxS + 1];    // first full row tile of each slot (prefix sum of count / 256)
+    __shared__ int base_all[kMaxS + 1];  // first row tile of each slot, partial tiles included
+    __shared__ int ragged[kMaxS];      // slots with a partial last tile, most rows first
+    __shared__ int n_ragged;
+    for (int s = threadIdx.x; s < S; s += 256) cnt_s[s] = offsets[s + 1] - offsets[s];
     __syncthreads();
     if (threadIdx.x == 0) {
-        int run = 0;
-        for (int t = 0; t < 256; ++t) {
-            int c = part[t];
-            part[t] = run;
-            run += c;
+        // counting sort of the partial tiles by occupied 32-row sub-tiles, 8 down to 1
+        int bucket[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+        int run = 0, run_all = 0;
+        for (int s = 0; s < S; ++s) {
+            base[s] = run;
+            base_all[s] = run_all;
+            run += cnt_s[s] / kBM;
+            run_all += (cnt_s[s] + kBM - 1) / kBM;
+            const int rem = cnt_s[s] % kBM;
+            if (rem) ++bucket[(rem + 31) / 32];
         }
-        tab[L.hdr] = run;
         base[S] = run;
+        base_all[S] = run_all;
+        int at = 0;
+        for (int b = 8; b >= 1; --b) {
+            const int c = bucket[b];
+            bucket[b] = at;
+            at += c;
+        }
+        n_ragged = at;
+        for (int s = 0; s < S; ++s) {
+            const int rem = cnt_s[s] % kBM;
+            if (rem) ragged[bucket[(rem + 31) / 32]++] = s;
+        }
+        tab[L.hdr] = run + at;
     }
     __syncthreads();
-    int run = part[threadIdx.x];
-    for (int s = s_lo; s < s_hi; ++s) {
-        base[s] = run;
-        run += (offsets[s + 1] - offsets[s] + kBM - 1) / kBM;
-    }
-    __syncthreads();
-    const int total_m = base[S];
+    const int total_full = base[S], nr = n_ragged, total_m = base_all[S];
     int4* lists = reinterpret_cast<int4*>(tab);
     for (int p = 0; p < 2; ++p) {
         const int NT = p == 0 ? nt_up : nt_down;
+        // few tiles per compute unit: the end of the launch decides, longest work first;
+        // many: keep the partial tile next to the full tiles that share its weight panel
+        const bool longest_first = total_m * NT < kLongestFirstBelow;
         for (int c = 0; c < 2; ++c) {
             const int nt_x = c == 0 ? (NT + kXcds - 1) / kXcds : NT / kXcds;
-            const int n = total_m * nt_x;
+            const int n_full = longest_first ? total_full * nt_x : 0, n = total_m * nt_x;
             for (int e = threadIdx.x; e < n; e += 256) {
-                int lo = 0, hi = S;  // largest s with base[s]*nt_x <= e (empty slots have equal bounds)
-                while (hi - lo > 1) {
-                    int mid = (lo + hi) >> 1;
-                    if (base[mid] * nt_x <= e) lo = mid; else hi = mid;
+                int4 ent;
+                if (!longest_first) {
+                    int lo = 0, hi = S;  // largest s with base_all[s]*nt_x <= e (empty slots have equal bounds)
+                    while (hi - lo > 1) {
+                        int mid = (lo + hi) >> 1;
+                        if (base_all[mid] * nt_x <= e) lo = mid; else hi = mid;
+                    }
+                    const int s = lo, mt_s = base_all[s + 1] - base_all[s];
+                    const int rem = e - base_all[s] * nt_x;
+                    const int ntl = rem / mt_s, mi = rem % mt_s;
+                    ent = make_int4(s, ntl, offsets[s] + mi * kBM, min(kBM, cnt_s[s] - mi * kBM));
+                } else if (e < n_full) {
+                    int lo = 0, hi = S;  // largest s with base[s]*nt_x <= e (slots without full tiles have equal bounds)
+                    while (hi - lo > 1) {
+                        int mid = (lo + hi) >> 1;
+                        if (base[mid] * nt_x <= e) lo = mid; else hi = mid;
+                    }
+                    const int s = lo, mt_s = base[s + 1] - base[s];
+                    const int rem = e - base[s] * nt_x;
+                    const int ntl = rem / mt_s, mi = rem % mt_s;
+                    ent = make_int4(s, ntl, offsets[s] + mi * kBM, kBM);
+                } else {
+                    const int q = e - n_full;
+                    const int s = ragged[q / nt_x];
+                    const int full = cnt_s[s] / kBM;
+                    ent = make_int4(s, q % nt_x, offsets[s] + full * kBM, cnt_s[s] - full * kBM);
                 }
-                const int s = lo, mt_s = base[s + 1] - base[s];
-                const int rem = e - base[s] * nt_x;
-                const int ntl = rem / mt_s, mi = rem % mt_s;
-                const int r0 = offsets[s], cnt = offsets[s + 1] - r0;
-                lists[L.list[p][c] + e] = make_int4(s, ntl, r0 + mi * kBM, min(kBM, cnt - mi * kBM));
+                lists[L.list[p][c] + e] = ent;
             }
         }
     }
