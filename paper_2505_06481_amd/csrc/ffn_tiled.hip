@@ -36,10 +36,13 @@ enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2 };
 constexpr int kBM = 256;  // token rows per tile
 constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
-#ifndef MMOE_TILED_NB
-#define MMOE_TILED_NB 2
+#ifndef MMOE_TILED_WM
+#define MMOE_TILED_WM 1
 #endif
-constexpr int kTiledNB = MMOE_TILED_NB;  // weight blocks per wavefront: 1 = eight wavefronts, 2 = four
+#ifndef MMOE_TILED_BAHEAD
+#define MMOE_TILED_BAHEAD (MMOE_TILED_WM == 1 ? 8 : 4)
+#endif
+constexpr int kTiledWM = MMOE_TILED_WM;  // wavefronts along the token rows: 1 = four wavefronts, 2 = eight
 constexpr int kXcds = 8;
 constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB: one step of the token operand
 constexpr int kStagesA = 3;
@@ -175,15 +178,17 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
     }
 }
 
-// NB = 32-row weight blocks per wavefront: 2 -> four wavefronts (one per SIMD), 1 -> eight
-// wavefronts (two per SIMD, so that one can issue matrix instructions while the other is
-// busy issuing loads).
-template <int MODE, int NB>
-__global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __restrict__ A,
-                                                             const int32_t* __restrict__ tab, int list_hi,
-                                                             int list_lo, const uint16_t* __restrict__ W0,
-                                                             const uint16_t* __restrict__ W1,
-                                                             void* __restrict__ out, int K, int N, int NT)
+// WM = wavefronts along the token rows.  1: four wavefronts (one per SIMD), each with all 256
+// token rows and 64 weight rows.  2: eight wavefronts (two per SIMD, so that one can issue
+// matrix instructions while the other is held up issuing loads or LDS writes), each with 128
+// token rows and 64 weight rows; the two wavefronts with the same weight rows load the same
+// weight fragments (the second load hits in the compute unit's L1).
+template <int MODE, int WM>
+__global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __restrict__ A,
+                                                            const int32_t* __restrict__ tab, int list_hi,
+                                                            int list_lo, const uint16_t* __restrict__ W0,
+                                                            const uint16_t* __restrict__ W1,
+                                                            void* __restrict__ out, int K, int N, int NT)
 {
     __shared__ __attribute__((aligned(1024))) char lds_a[kStagesA * kTileBytes];
 
@@ -206,13 +211,18 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
     constexpr int kFeat = MODE == kTModeSwigluH ? kBN / 2 : kBN;  // output features per tile
     const int n0 = nt * kFeat;
 
-    constexpr int kWaves = 8 / NB;
+    constexpr int NB = 2;             // 32-row weight blocks per wavefront
+    constexpr int kWaves = 4 * WM;
     constexpr int kThreads = kWaves * 64;
+    constexpr int kNJ = 8 / WM;       // 32-row token sub-tiles per wavefront
+    constexpr int kBAhead = MMOE_TILED_BAHEAD;  // 16-k slices between a weight fragment's load and its use (4 or 8)
     constexpr int kNP = 2048 / kThreads;  // 16-byte pieces of a token tile per thread
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps bases in scalar registers
     const int lr = lane & 31;
+    const int wn = wave & 3;          // which 64 weight rows of the tile
+    const int wm = wave >> 2;         // which kNJ token sub-tiles of the tile
 
     // ---- token operand: global -> registers -> LDS ----------------------------------------------
     // Piece id = i*kThreads + tid (i < kNP) of a [256 rows][8 pieces of 16 bytes] tile: 8
@@ -243,25 +253,15 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
     };
 
     // ---- weight operand: fragment-packed pool -> registers ------------------------------------------
-    // NB = 2: wavefront w owns weight rows [64w, 64w+64) of the tile, two 32-row blocks; for the
-    // gated product they are block (n0 + 32w)/32 of W1 (gate) and the same block of W3 (up), so
-    // that a lane holds matching gate and up values.  NB = 1: wavefront w owns one block; for the
-    // gated product wavefronts 2p and 2p+1 hold the gate and the up values of features
-    // [n0 + 32p, n0 + 32p + 32) and meet in the epilogue.  Fragment ks of a block is 1 KB at ks*1024.
+    // A wavefront owns weight rows [64 wn, 64 wn + 64) of the tile, two 32-row blocks; for the
+    // gated product they are block (n0 + 32 wn)/32 of W1 (gate) and the same block of W3 (up), so
+    // that a lane holds matching gate and up values.  Fragment ks of a block is 1 KB at ks*1024.
     const size_t frag_bytes_per_block = (size_t)(K / 16) * 1024;
-    const int fgrp = NB == 2 ? wave : (wave >> 1);      // gated: 32-feature group of this wavefront
-    const bool up_role = NB == 1 && (wave & 1);         // gated, NB = 1: this wavefront multiplies W3
     const char* wb[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-        const uint16_t* w = W0;
-        int nb;
-        if (MODE == kTModeSwigluH) {
-            if (NB == 2 ? i == 1 : up_role) w = W1;
-            nb = (n0 + fgrp * 32) / 32;
-        } else {
-            nb = (n0 + wave * (32 * NB) + i * 32) / 32;
-        }
+        const uint16_t* w = (MODE == kTModeSwigluH && i == 1) ? W1 : W0;
+        const int nb = MODE == kTModeSwigluH ? (n0 + wn * 32) / 32 : (n0 + wn * 64 + i * 32) / 32;
         wb[i] = reinterpret_cast<const char*>(w) + ((size_t)s * (N / 32) + nb) * frag_bytes_per_block + lane * 16;
     }
 
@@ -270,18 +270,20 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
     // the 8 k values that the packed weight fragment pairs with it.
     int frag_off[4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) frag_off[kk] = lr * 128 + ((((lane >> 5) * 4 + kk) ^ ((lr >> 1) & 7)) << 4);
+    for (int kk = 0; kk < 4; ++kk)
+        frag_off[kk] = (wm * kNJ * 32 + lr) * 128 + ((((lane >> 5) * 4 + kk) ^ ((lr >> 1) & 7)) << 4);
 
-    f32x16 acc[8][NB];  // [token tile][weight block]
+    f32x16 acc[kNJ][NB];  // [token sub-tile][weight block]
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < kNJ; ++j)
 #pragma unroll
         for (int i = 0; i < NB; ++i)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
 
-    // Main loop, instantiated for NJ = number of 32-row token sub-tiles that hold rows (8 for
-    // every tile but the last one of a slot).
+    // Main loop, instantiated for NJ = number of this wavefront's 32-row token sub-tiles that
+    // hold rows (all kNJ for every tile but the last one of a slot; a wavefront with none still
+    // stages tokens and meets the barriers).
     //
     // Pipeline (k step t = 64 k = four 16-k slices; step t's tokens live in LDS stage t mod 3):
     //   weights   slice g is loaded straight into registers 8 slices (two steps) before use;
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
         struct BFrags {
             u32x4 b[NB];
         };
-        bf16x8 fa[NJ];
+        bf16x8 fa[NJ > 0 ? NJ : 1];
         auto frag_ptr = [&](int stage, int kk) { return lds_a + stage * kTileBytes + frag_off[kk]; };
         auto load_bf = [&](BFrags& fr, int g) {
             const size_t o = (size_t)min(g, last_slice) * 1024;  // past the end: a harmless reload
@@ -333,12 +335,12 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
         };
 
         ATile ra[2];
-        BFrags bq[8];
+        BFrags bq[kBAhead];
         // prologue: steps 0..2 into the three stages, steps 3 and 4 on their way into registers
         load_a(ra[0], 0);
         load_a(ra[1], 1);
 #pragma unroll
-        for (int g = 0; g < 8; ++g) load_bf(bq[g], g);
+        for (int g = 0; g < kBAhead; ++g) load_bf(bq[g], g);
         store_a(ra[0], 0);
         load_a(ra[0], min(2, last));
         store_a(ra[1], 1);
@@ -359,12 +361,12 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
                 const int t = kt + u;
                 const int stn = st == kStagesA - 1 ? 0 : st + 1;
                 const int g = 4 * t;
-                slice(bq[4 * u + 0], frag_ptr(st, 1), g + 8);
-                slice(bq[4 * u + 1], frag_ptr(st, 2), g + 9);
-                slice(bq[4 * u + 2], frag_ptr(st, 3), g + 10);
+                slice(bq[(4 * u + 0) % kBAhead], frag_ptr(st, 1), g + kBAhead);
+                slice(bq[(4 * u + 1) % kBAhead], frag_ptr(st, 2), g + kBAhead + 1);
+                slice(bq[(4 * u + 2) % kBAhead], frag_ptr(st, 3), g + kBAhead + 2);
                 // last slice of the step: its fragments are in flight or in registers
                 {
-                    BFrags& fb = bq[4 * u + 3];
+                    BFrags& fb = bq[(4 * u + 3) % kBAhead];
                     const char* next = frag_ptr(stn, 0);
 #pragma unroll
                     for (int j = 0; j < NH; ++j) mma_roll(j, fb, next);
@@ -380,7 +382,7 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
                     load_a(ra[(u + 1) & 1], min(t + 5, last));
 #pragma unroll
                     for (int j = NH; j < NJ; ++j) mma_roll(j, fb, next);
-                    load_bf(fb, g + 11);
+                    load_bf(fb, g + kBAhead + 3);
 #pragma unroll
                     for (int q = 0; q < (kNP > NJ - NH ? kNP : NJ - NH); ++q) {
                         if (q < NJ - NH) {
@@ -398,15 +400,16 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
             }
         }
     };
-    switch (min(8, (cnt + 31) / 32)) {
-        case 8: run(std::integral_constant<int, 8>{}); break;
-        case 7: run(std::integral_constant<int, 7>{}); break;
-        case 6: run(std::integral_constant<int, 6>{}); break;
-        case 5: run(std::integral_constant<int, 5>{}); break;
+    switch (max(0, min(kNJ, (cnt + 31) / 32 - wm * kNJ))) {  // uniform over the wavefront
+        case 8: if constexpr (kNJ >= 8) run(std::integral_constant<int, 8>{}); break;
+        case 7: if constexpr (kNJ >= 8) run(std::integral_constant<int, 7>{}); break;
+        case 6: if constexpr (kNJ >= 8) run(std::integral_constant<int, 6>{}); break;
+        case 5: if constexpr (kNJ >= 8) run(std::integral_constant<int, 5>{}); break;
         case 4: run(std::integral_constant<int, 4>{}); break;
         case 3: run(std::integral_constant<int, 3>{}); break;
         case 2: run(std::integral_constant<int, 2>{}); break;
-        default: run(std::integral_constant<int, 1>{}); break;
+        case 1: run(std::integral_constant<int, 1>{}); break;
+        default: if constexpr (WM > 1) run(std::integral_constant<int, 0>{}); break;
     }
 
     // ---- epilogue -------------------------------------------------------------------------------
@@ -421,11 +424,11 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
     constexpr int kLpr = kRowB / 16;                  // lanes that read one row back
     constexpr int kRpi = 64 / kLpr;                   // rows per read-back instruction
     constexpr int kChunks = MODE == kTModeSwigluH ? 1 : NB;       // 32-feature chunks this wavefront stores
-    constexpr bool kPaired = MODE == kTModeSwigluH && NB == 1;    // gate and up live in two wavefronts
-    const int wfeat = MODE == kTModeSwigluH ? fgrp * 32 : wave * (32 * NB);
+    const int wfeat = MODE == kTModeSwigluH ? wn * 32 : wn * 64;
+    const int wrow = wm * kNJ * 32;                   // first tile row of this wavefront
     __shared__ __attribute__((aligned(16))) char lds_epi[kWaves][32 * (32 * 4 + 16)];
     char* ebuf = lds_epi[wave];
-    char* const obase = reinterpret_cast<char*>(out) + ((size_t)r0 * N + n0 + wfeat) * kEsz +
+    char* const obase = reinterpret_cast<char*>(out) + ((size_t)(r0 + wrow) * N + n0 + wfeat) * kEsz +
                         (size_t)(lane / kLpr) * N * kEsz + (lane % kLpr) * 16;
     // o[4q + e]: the 16 finished values of this lane for token sub-tile j, feature chunk c
     auto emit = [&](int j, int c, const float (&o)[16]) {
@@ -445,61 +448,23 @@ __global__ __launch_bounds__(512 / NB, 1) void tiled_kernel(const uint16_t* __re
         for (int it = 0; it < 32 / kRpi; ++it) {
             const int row = it * kRpi + lane / kLpr;
             const u32x4 v = *reinterpret_cast<const u32x4*>(ebuf + row * kPitch + (lane % kLpr) * 16);
-            if (j * 32 + row < cnt)
+            if (wrow + j * 32 + row < cnt)
                 *reinterpret_cast<u32x4*>(obase + ((size_t)(j * 32 + it * kRpi) * N + c * 32) * kEsz) = v;
         }
     };
-    if (!kPaired) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if (j * 32 >= cnt) break;  // uniform
+    for (int j = 0; j < kNJ; ++j) {
+        if (wrow + j * 32 >= cnt) break;  // uniform over the wavefront
 #pragma unroll
-            for (int c = 0; c < kChunks; ++c) {
-                float o[16];
+        for (int c = 0; c < kChunks; ++c) {
+            float o[16];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    if (MODE == kTModeSwigluH) o[e] = silu_mul_t(acc[j][0][e], acc[j][NB - 1][e]);
-                    else if (MODE == kTModeReluH) o[e] = fmaxf(acc[j][c][e], 0.0f);
-                    else o[e] = acc[j][c][e];
-                }
-                emit(j, c, o);
+            for (int e = 0; e < 16; ++e) {
+                if (MODE == kTModeSwigluH) o[e] = silu_mul_t(acc[j][0][e], acc[j][1][e]);
+                else if (MODE == kTModeReluH) o[e] = fmaxf(acc[j][c][e], 0.0f);
+                else o[e] = acc[j][c][e];
             }
-        }
-    } else {
-        // The up wavefront hands its accumulators to the gate wavefront of the same 32 features
-        // through the token stages, which nobody reads any more: four token sub-tiles per round,
-        // 4 KB per sub-tile, in accumulator order (so both sides use the same lane mapping).
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            if (r * 128 >= cnt) break;  // uniform over the workgroup
-            char* xb = lds_a + (size_t)fgrp * (4 * 4096) + lane * 16;
-            if (up_role) {
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        *reinterpret_cast<f32x4*>(xb + (jj * 4 + q) * 1024) =
-                            f32x4{acc[4 * r + jj][0][4 * q], acc[4 * r + jj][0][4 * q + 1], acc[4 * r + jj][0][4 * q + 2],
-                                  acc[4 * r + jj][0][4 * q + 3]};
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            if (!up_role) {
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const int j = 4 * r + jj;
-                    if (j * 32 >= cnt) break;
-                    float o[16];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x4 u = *reinterpret_cast<const f32x4*>(xb + (jj * 4 + q) * 1024);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[4 * q + e] = silu_mul_t(acc[j][0][4 * q + e], u[e]);
-                    }
-                    emit(j, 0, o);
-                }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            emit(j, c, o);
         }
     }
 }
@@ -527,19 +492,19 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets
     int nt_up, nt_down;
     tiled_nts(s, nt_up, nt_down);
     const TileLists L = tile_lists(P, s.S, nt_up, nt_down);
-    dim3 block(512 / kTiledNB);
+    dim3 block(256 * kTiledWM);
     const uint16_t* nul = nullptr;
     hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, L);
     if (s.act == MMOE_SWIGLU)
-        hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH, kTiledNB>), dim3(L.cap[0] * kXcds), block, 0, st,
+        hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH, kTiledWM>), dim3(L.cap[0] * kXcds), block, 0, st,
                            (const uint16_t*)Xg, tab, L.list[0][0], L.list[0][1], (const uint16_t*)W1p,
                            (const uint16_t*)W3p, H, d, f, nt_up);
     else
-        hipLaunchKernelGGL((tiled_kernel<kTModeReluH, kTiledNB>), dim3(L.cap[0] * kXcds), block, 0, st,
+        hipLaunchKernelGGL((tiled_kernel<kTModeReluH, kTiledWM>), dim3(L.cap[0] * kXcds), block, 0, st,
                            (const uint16_t*)Xg, tab, L.list[0][0], L.list[0][1], (const uint16_t*)W1p, nul, H, d, f,
                            nt_up);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    hipLaunchKernelGGL((tiled_kernel<kTModePlainF32, kTiledNB>), dim3(L.cap[1] * kXcds), block, 0, st,
+    hipLaunchKernelGGL((tiled_kernel<kTModePlainF32, kTiledWM>), dim3(L.cap[1] * kXcds), block, 0, st,
                        (const uint16_t*)H, tab, L.list[1][0], L.list[1][1], (const uint16_t*)W2p, nul, (void*)Yg, f, d,
                        nt_down);
     return launch_status();
