@@ -26,6 +26,32 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM traffic of the dominant kernels, from two rocprofv3 --pmc passes over this script
+# (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch; summaries under profiles/), each scaled by
+# what the same counter reads for a plain 1 GiB device copy (--copy-calibration): FETCH_SIZE
+# reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).  The figures belong
+# to one version of the kernel source; with any other version `traffic` is null.
+TRAFFIC = {
+    "ffn_tiled.hip": {"sha256": "", "workload": "mixtral_prefill_bf16_v2_t8192",
+                      "fetch_bytes": 0, "write_bytes": 0},
+    "ffn_skinny.hip": {"sha256": "", "workload": "mixtral_decode_bf16_v2_t64",
+                       "fetch_bytes": 0, "write_bytes": 0},
+}
+
+
+def measured_traffic(source, workload):
+    """Counter-derived HBM bytes (read + written) per launch of the up-product kernel, or None
+    if the kernel source has changed since the counters were taken."""
+    import hashlib
+
+    rec = TRAFFIC[source]
+    path = os.path.join(ROOT, "paper_2505_06481_amd", "csrc", source)
+    with open(path, "rb") as fh:
+        digest = hashlib.sha256(fh.read()).hexdigest()
+    if digest != rec["sha256"] or workload != rec["workload"]:
+        return None
+    return rec["fetch_bytes"] + rec["write_bytes"]
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -132,13 +158,16 @@ def roofline(cfg, res, skinny):
         alg_bytes = active * nw * d * f * es + P * d * es + P * f * es
         ach = alg_bytes / dur_s / 1e9
         return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
-                    traffic=None, kernel=("skinny_frag_kernel" if cfg.dtype == "bf16" else "skinny_kernel") + " (up product)", bytes_per_launch=alg_bytes,
+                    traffic=measured_traffic("ffn_skinny.hip", cfg.name),
+                    kernel=("skinny_frag_kernel" if cfg.dtype == "bf16" else "skinny_kernel") + " (up product)",
+                    bytes_per_launch=alg_bytes,
                     avg_launch_ms=dur_s * 1e3)
     flops = 2.0 * P * d * f * nw
     ach = flops / dur_s / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_MFMA_TFLOPS
-    return dict(bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak, traffic=None,
-                kernel="tiled_kernel (up product)", flops_per_launch=flops, avg_launch_ms=dur_s * 1e3)
+    return dict(bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
+                traffic=measured_traffic("ffn_tiled.hip", cfg.name), kernel="tiled_kernel (up product)",
+                flops_per_launch=flops, avg_launch_ms=dur_s * 1e3)
 
 
 def cpu_baseline(cfg, inp, n_tokens):
