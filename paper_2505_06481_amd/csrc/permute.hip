@@ -85,6 +85,33 @@ __global__ __launch_bounds__(kPermThreads) void slot_scan_kernel(const int32_t* 
     }
 }
 
+// Stable placement of up to 64 pairs, one per lane, behind the pairs placed before them:
+// lane l's peers are the lanes that hold the same slot, found with one ballot per bit of the
+// slot id; its row is the slot's cursor plus the number of peers in lower lanes; the lowest
+// peer then advances the cursor.  `cur` is this wavefront's private cursor row in LDS, and
+// LDS operations of one wavefront execute in program order.
+__device__ __forceinline__ void place_pairs(volatile int* cur, int s, bool valid, int lane, int sbits, int p,
+                                            int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm)
+{
+    unsigned long long m = __ballot(valid);
+    for (int b = 0; b < sbits; ++b) {
+        const bool bit = (s >> b) & 1;
+        const unsigned long long bal = __ballot(bit);
+        m &= bit ? bal : ~bal;
+    }
+    const int rank = __popcll(m & ((1ull << lane) - 1ull));
+    int base = 0;
+    if (valid) {
+        base = cur[s];
+        const int r = base + rank;
+        perm[r] = p;
+        inv_perm[p] = r;
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (valid && rank == 0) cur[s] = base + __popcll(m);
+    __builtin_amdgcn_wave_barrier();
+}
+
 // perm / inv_perm: stable ranks from ballots.
 __global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_t* __restrict__ slot,
                                                                     const int32_t* __restrict__ blk_base,
@@ -95,6 +122,7 @@ __global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_
     __shared__ int cursor[kPermWaves][kMaxS];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
+    const int sbits = 32 - __clz(max(S - 1, 1));  // bits of a slot id
     for (int i = threadIdx.x; i < kPermWaves * S; i += kPermThreads) wtot[i / S][i % S] = 0;
     __syncthreads();
     const int wbase = blockIdx.x * kPermChunk + wave * kPairsPerWave;
@@ -118,23 +146,8 @@ __global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_
     for (int i0 = 0; i0 < kPairsPerWave; i0 += kWave) {
         int p = wbase + i0 + lane;
         bool valid = p < P;
-        int s = valid ? slot[p] : -1;
-        unsigned long long todo = __ballot(valid);
-        while (todo) {
-            int leader = __ffsll((long long)todo) - 1;
-            int s0 = __shfl(s, leader, kWave);
-            unsigned long long m = __ballot(valid && s == s0);
-            if (valid && s == s0) {
-                int rank = __popcll(m & ((1ull << lane) - 1ull));
-                int r = cur[s0] + rank;
-                perm[r] = p;
-                inv_perm[p] = r;
-            }
-            __builtin_amdgcn_wave_barrier();
-            if (lane == leader) cur[s0] = cur[s0] + __popcll(m);
-            __builtin_amdgcn_wave_barrier();
-            todo &= ~m;
-        }
+        int s = valid ? slot[p] : 0;
+        place_pairs(cur, s, valid, lane, sbits, p, perm, inv_perm);
     }
 }
 
@@ -151,6 +164,7 @@ __global__ __launch_bounds__(kPermThreads) void slot_group_small_kernel(
     __shared__ int myslot[kPermChunk];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
+    const int sbits = 32 - __clz(max(S - 1, 1));  // bits of a slot id
     for (int i = threadIdx.x; i < kPermWaves * S; i += kPermThreads) wtot[i / S][i % S] = 0;
     __syncthreads();
     const int wbase = wave * kPairsPerWave;
@@ -208,23 +222,8 @@ __global__ __launch_bounds__(kPermThreads) void slot_group_small_kernel(
         int p = wbase + i0 + lane;
         bool valid = p < P;
         if (!__ballot(valid)) break;  // uniform over the wavefront
-        int s = valid ? myslot[p] : -1;
-        unsigned long long todo = __ballot(valid);
-        while (todo) {
-            int leader = __ffsll((long long)todo) - 1;
-            int s0 = __shfl(s, leader, kWave);
-            unsigned long long m = __ballot(valid && s == s0);
-            if (valid && s == s0) {
-                int rank = __popcll(m & ((1ull << lane) - 1ull));
-                int r = cur[s0] + rank;
-                perm[r] = p;
-                inv_perm[p] = r;
-            }
-            __builtin_amdgcn_wave_barrier();
-            if (lane == leader) cur[s0] = cur[s0] + __popcll(m);
-            __builtin_amdgcn_wave_barrier();
-            todo &= ~m;
-        }
+        int s = valid ? myslot[p] : 0;
+        place_pairs(cur, s, valid, lane, sbits, p, perm, inv_perm);
     }
 }
 

@@ -35,58 +35,12 @@ template <> struct Vec4<uint16_t> {
     }
 };
 
-// One workgroup per token; wavefront w scores experts w, w+8, ...  A token's dot product
-// with one expert is never split between wavefronts, so the summation order is the
-// contract's whatever the launch shape.  Four vectors per lane are fetched at a time to
-// keep eight loads in flight.
-template <typename T>
-__global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
-    const T* __restrict__ X, const int32_t* __restrict__ vid, const T* __restrict__ Wr,
-    const float* __restrict__ br, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d,
-    int V, int E, int k)
+// The k winners among E logits in LDS, found by one wavefront: lane l looks after experts
+// l, l+64, l+128, l+192; k arg-max reductions, ties to the lower index; coefficients =
+// softmax over the selected logits.
+__device__ __forceinline__ void select_topk(const float* __restrict__ lds_logit, int lane, int E, int k, int t,
+                                            int32_t* __restrict__ topk_idx, float* __restrict__ topk_w)
 {
-    __shared__ float lds_logit[kMaxE];
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int t = blockIdx.x;
-
-    const int v = min(max(vid[t], 0), V - 1);  // out-of-range ids are the caller's error; stay in bounds
-    const T* x = X + (size_t)t * d;
-    const int nvec = d / 4;  // a multiple of 64: d is a multiple of 256
-
-    for (int e = wave; e < E; e += kRouteWaves) {
-        const T* w = Wr + ((size_t)v * E + e) * d;
-        float acc = 0.0f;
-        int q = lane;
-        for (; q + 3 * kWave < nvec; q += 4 * kWave) {  // ascending i within the lane
-            float xv[4][4], wv[4][4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                Vec4<T>::load(x + 4 * (q + u * kWave), xv[u]);
-                Vec4<T>::load(w + 4 * (q + u * kWave), wv[u]);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) acc = __builtin_fmaf(xv[u][c], wv[u][c], acc);
-        }
-        for (; q < nvec; q += kWave) {
-            float xv[4], wv[4];
-            Vec4<T>::load(x + 4 * q, xv);
-            Vec4<T>::load(w + 4 * q, wv);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc = __builtin_fmaf(xv[c], wv[c], acc);
-        }
-        float p = acc;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) p = p + __shfl_xor(p, off, kWave);
-        if (br) p = p + br[(size_t)v * E + e];
-        if (lane == 0) lds_logit[e] = p;
-    }
-    __syncthreads();
-    if (wave != 0) return;
-
-    // each lane looks after experts lane, lane+64, lane+128, lane+192
     constexpr int kPerLane = kMaxE / kWave;
     float mine[kPerLane];
 #pragma unroll
@@ -141,9 +95,176 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     }
 }
 
+// One workgroup per token; wavefront w scores experts w, w+8, ...  A token's dot product
+// with one expert is never split between wavefronts, so the summation order is the
+// contract's whatever the launch shape.  Four vectors per lane are fetched at a time to
+// keep eight loads in flight.
+template <typename T>
+__global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
+    const T* __restrict__ X, const int32_t* __restrict__ vid, const T* __restrict__ Wr,
+    const float* __restrict__ br, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d,
+    int V, int E, int k)
+{
+    __shared__ float lds_logit[kMaxE];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int t = blockIdx.x;
+
+    const int v = min(max(vid[t], 0), V - 1);  // out-of-range ids are the caller's error; stay in bounds
+    const T* x = X + (size_t)t * d;
+    const int nvec = d / 4;  // a multiple of 64: d is a multiple of 256
+
+    for (int e = wave; e < E; e += kRouteWaves) {
+        const T* w = Wr + ((size_t)v * E + e) * d;
+        float acc = 0.0f;
+        int q = lane;
+        for (; q + 3 * kWave < nvec; q += 4 * kWave) {  // ascending i within the lane
+            float xv[4][4], wv[4][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                Vec4<T>::load(x + 4 * (q + u * kWave), xv[u]);
+                Vec4<T>::load(w + 4 * (q + u * kWave), wv[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc = __builtin_fmaf(xv[u][c], wv[u][c], acc);
+        }
+        for (; q < nvec; q += kWave) {
+            float xv[4], wv[4];
+            Vec4<T>::load(x + 4 * q, xv);
+            Vec4<T>::load(w + 4 * q, wv);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc = __builtin_fmaf(xv[c], wv[c], acc);
+        }
+        float p = acc;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) p = p + __shfl_xor(p, off, kWave);
+        if (br) p = p + br[(size_t)v * E + e];
+        if (lane == 0) lds_logit[e] = p;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+
+    select_topk(lds_logit, lane, E, k, t, topk_idx, topk_w);
+}
+
+// Four consecutive elements as loaded (bf16 stays packed until it is used, which halves the
+// registers a pending load occupies).
+template <typename T> struct Raw4;
+template <> struct Raw4<float> {
+    typedef f32x4 type;
+    static __device__ __forceinline__ float get(const type& r, int q) { return r[q]; }
+};
+template <> struct Raw4<uint16_t> {
+    typedef u32x2 type;
+    static __device__ __forceinline__ float get(const type& r, int q)
+    {
+        return (q & 1) ? __uint_as_float(r[q >> 1] & 0xFFFF0000u) : __uint_as_float(r[q >> 1] << 16);
+    }
+};
+
+// Throughput variant for large batches: one wavefront per token.  The token's elements
+// stay in registers (NC chunks of 256, d = 256*NC exactly, so that every load of a pass is
+// issued before the first one is waited for) and the wavefront walks the experts
+// two at a time, so that the token row crosses the memory pipeline once instead of once
+// per expert.  Each (token, expert) sum is formed by one wavefront in the contract's order:
+// the results are bit-identical to route_kernel's.
+constexpr int kRouteTokWaves = 4;
+constexpr int kRouteTokMinT = 512;  // batches at least this large use the wavefront-per-token kernel
+
+template <typename T, int NC>
+__global__ __launch_bounds__(kRouteTokWaves* kWave) void route_token_kernel(
+    const T* __restrict__ X, const int32_t* __restrict__ vid, const T* __restrict__ Wr,
+    const float* __restrict__ br, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d,
+    int V, int E, int k)
+{
+    __shared__ float lds_logit[kRouteTokWaves][kMaxE];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int t = blockIdx.x * kRouteTokWaves + wave;
+    if (t >= Tn) return;  // uniform over the wavefront; no workgroup barrier below
+
+    const int v = min(max(vid[t], 0), V - 1);
+    const T* x = X + (size_t)t * d + 4 * lane;
+    typedef typename Raw4<T>::type raw_t;
+    raw_t xv[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) xv[c] = *reinterpret_cast<const raw_t*>(x + 256 * c);
+
+    const T* wv0 = Wr + (size_t)v * E * d + 4 * lane;
+    float* mylogit = lds_logit[wave];
+    for (int e = 0; e < E; e += 2) {
+        const bool two = e + 1 < E;
+        const T* w0 = wv0 + (size_t)e * d;
+        const T* w1 = wv0 + (size_t)(two ? e + 1 : e) * d;
+        float a0 = 0.0f, a1 = 0.0f;
+        raw_t p0[NC], p1[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            p0[c] = *reinterpret_cast<const raw_t*>(w0 + 256 * c);
+            p1[c] = *reinterpret_cast<const raw_t*>(w1 + 256 * c);
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {  // ascending i within the lane
+                const float xq = Raw4<T>::get(xv[c], q);
+                a0 = __builtin_fmaf(xq, Raw4<T>::get(p0[c], q), a0);
+                a1 = __builtin_fmaf(xq, Raw4<T>::get(p1[c], q), a1);
+            }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            a0 = a0 + __shfl_xor(a0, off, kWave);
+            a1 = a1 + __shfl_xor(a1, off, kWave);
+        }
+        if (br) {
+            a0 = a0 + br[(size_t)v * E + e];
+            if (two) a1 = a1 + br[(size_t)v * E + e + 1];
+        }
+        if (lane == 0) {
+            mylogit[e] = a0;
+            if (two) mylogit[e + 1] = a1;
+        }
+    }
+    // lane 0's LDS writes before every lane's reads: one wavefront's LDS operations execute in
+    // program order, the fence keeps the compiler from moving them
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    select_topk(mylogit, lane, E, k, t, topk_idx, topk_w);
+}
+
 int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const void* Wr, const float* br,
                  int32_t* topk_idx, float* topk_w, hipStream_t st)
 {
+    // Large batches of a common hidden size: a wavefront per token (the token row is read
+    // once); otherwise a workgroup per token (lower latency, any d).
+    const int nc = s.d_model / 256;
+    const bool tok_nc = nc == 1 || nc == 2 || nc == 3 || nc == 4 || nc == 6 || nc == 8 || nc == 12 || nc == 16;
+    if (s.T >= kRouteTokMinT && tok_nc && s.d_model % 256 == 0) {
+        dim3 grid((s.T + kRouteTokWaves - 1) / kRouteTokWaves), block(kRouteTokWaves * kWave);
+#define MMOE_ROUTE_TOK(NC)                                                                                          \
+    case NC:                                                                                                        \
+        if (s.dtype == MMOE_BF16)                                                                                   \
+            hipLaunchKernelGGL((route_token_kernel<uint16_t, NC>), grid, block, 0, st, (const uint16_t*)X, vid,     \
+                               (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k);       \
+        else                                                                                                        \
+            hipLaunchKernelGGL((route_token_kernel<float, NC>), grid, block, 0, st, (const float*)X, vid,           \
+                               (const float*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k);          \
+        break
+        switch (nc) {
+            MMOE_ROUTE_TOK(1);
+            MMOE_ROUTE_TOK(2);
+            MMOE_ROUTE_TOK(3);
+            MMOE_ROUTE_TOK(4);
+            MMOE_ROUTE_TOK(6);
+            MMOE_ROUTE_TOK(8);
+            MMOE_ROUTE_TOK(12);
+            default: MMOE_ROUTE_TOK(16);
+        }
+#undef MMOE_ROUTE_TOK
+        return launch_status();
+    }
     dim3 grid(s.T), block(kRouteWaves * kWave);
     if (s.dtype == MMOE_BF16)
         hipLaunchKernelGGL(route_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)X, vid,

@@ -80,6 +80,9 @@ SMALL = [
     synth.Config("t_bf16_skew", 1500, 256, 256, 4, 8, 2, "bf16", "swiglu", seed=8, vid_mode="zipf",
                  bias_alpha=1.0),
     synth.Config("t_bf16_topk_all", 400, 256, 256, 1, 3, 3, "bf16", "swiglu", seed=9),   # top_k = E
+    # batches large enough for the wavefront-per-token router, odd expert counts, fp32 and bf16
+    synth.Config("r_f32_odd_e", 600, 512, 256, 2, 5, 2, "f32", "swiglu", seed=17, bias_alpha=0.7),
+    synth.Config("r_bf16_odd_e", 530, 1536, 256, 3, 7, 2, "bf16", "relu", seed=18, bias_alpha=0.3),
 ]
 
 
@@ -107,6 +110,7 @@ def test_edge_cases(mm, gc, oracle):
     assert list(ref["topk_idx"][7]) == [0, 1, 2]
     # E above one wavefront's width, k = 8
     staged_vs_oracle(mm, gc, oracle, synth.Config("wide_e", 40, 256, 256, 1, 130, 8, "bf16", "relu", seed=13))
+    staged_vs_oracle(mm, gc, oracle, synth.Config("wide_e_many", 515, 256, 256, 1, 130, 8, "bf16", "relu", seed=19))
 
 
 def test_validate_inputs(mm, gc):
