@@ -39,13 +39,17 @@ constexpr int kBK = 64;
 #ifndef MMOE_TILED_WM
 #define MMOE_TILED_WM 1
 #endif
+#ifndef MMOE_TILED_DMA
+#define MMOE_TILED_DMA 1
+#endif
 #ifndef MMOE_TILED_BAHEAD
-#define MMOE_TILED_BAHEAD (MMOE_TILED_WM == 1 ? 8 : 4)
+#define MMOE_TILED_BAHEAD (MMOE_TILED_WM == 1 ? (MMOE_TILED_DMA ? 16 : 8) : 4)
 #endif
 constexpr int kTiledWM = MMOE_TILED_WM;  // wavefronts along the token rows: 1 = four wavefronts, 2 = eight
 constexpr int kXcds = 8;
 constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB: one step of the token operand
-constexpr int kStagesA = 3;
+constexpr bool kDmaA = MMOE_TILED_DMA;     // token rows: global -> LDS copies without staging registers
+constexpr int kStagesA = kDmaA ? 4 : 3;    // LDS ring of token tiles
 constexpr int kLongestFirstBelow = 8 * 256;  // tiles of a product: below this, partial tiles go last
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -238,6 +242,30 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
     // LDS position of piece i: row*128 + swizzled piece; (row >> 1) & 7 does not depend on i, so
     // the positions are one register plus multiples of kThreads*16
     const int a_lds0 = (tid >> 3) * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
+    // Copy variant: instruction i of a wavefront writes its 64 pieces to 1 KB of consecutive LDS
+    // addresses (M0 + 16*lane), 8 rows of 128 bytes, so the swizzle moves to the global side:
+    // the lane that fills physical piece q of a row fetches logical piece q ^ ((row >> 1) & 7).
+    uint32_t a_goff[kNP];
+#pragma unroll
+    for (int i = 0; i < kNP; ++i) {
+        const int row = i * (kThreads / 8) + (tid >> 3);
+        a_goff[i] = (uint32_t)min(row, cnt - 1) * (uint32_t)K * 2u + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
+    }
+    // The copies are written in assembly so that the compiler's wait-count bookkeeping does not
+    // see them (it would drain every load in flight before each LDS read); the waits that order
+    // them are written out next to the barriers.  M0 is only used here.
+    auto copy_a = [&](int stage, int kt) {
+        const char* ab = a_base + (size_t)kt * (kBK * 2);
+#pragma unroll
+        for (int i = 0; i < kNP; ++i) {
+            const uint32_t dst =
+                (uint32_t)(uintptr_t)(lptr_t)(lds_a + stage * kTileBytes + (i * kThreads + wave * 64) * 16);
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                         :
+                         : "v"(a_goff[i]), "s"(ab), "s"(dst)
+                         : "m0", "memory");
+        }
+    };
     struct ATile {
         u32x4 v[kNP];
     };
@@ -336,18 +364,31 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
 
         ATile ra[2];
         BFrags bq[kBAhead];
-        // prologue: steps 0..2 into the three stages, steps 3 and 4 on their way into registers
-        load_a(ra[0], 0);
-        load_a(ra[1], 1);
+        if constexpr (kDmaA) {
+            // prologue: copies of steps 0..3 into the four stages, then the first weight fragments.
+            // Order matters for the written-out waits: at least 16 loads follow the copies of step
+            // 1 (the copies of steps 2 and 3), so vmcnt(16 + weight loads) leaves steps 0 and 1 landed.
+            copy_a(0, 0);
+            copy_a(1, min(1, last));
+            copy_a(2, min(2, last));
+            copy_a(3, min(3, last));
 #pragma unroll
-        for (int g = 0; g < kBAhead; ++g) load_bf(bq[g], g);
-        store_a(ra[0], 0);
-        load_a(ra[0], min(2, last));
-        store_a(ra[1], 1);
-        load_a(ra[1], min(3, last));
-        store_a(ra[0], 2);
-        load_a(ra[0], min(4, last));
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            for (int g = 0; g < kBAhead; ++g) load_bf(bq[g], g);
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * kNP + NB * kBAhead) : "memory");
+        } else {
+            // prologue: steps 0..2 into the three stages, steps 3 and 4 on their way into registers
+            load_a(ra[0], 0);
+            load_a(ra[1], 1);
+#pragma unroll
+            for (int g = 0; g < kBAhead; ++g) load_bf(bq[g], g);
+            store_a(ra[0], 0);
+            load_a(ra[0], min(2, last));
+            store_a(ra[1], 1);
+            load_a(ra[1], min(3, last));
+            store_a(ra[0], 2);
+            load_a(ra[0], min(4, last));
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        }
         {
             const char* p0 = frag_ptr(0, 0);
 #pragma unroll
@@ -355,9 +396,10 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
         }
 
         int st = 0;  // LDS stage of step kt
-        for (int kt = 0; kt < nkt; kt += 2) {
+        constexpr int kUnroll = kBAhead >= 8 ? kBAhead / 4 : 2;  // steps per trip: the weight ring is indexed statically
+        for (int kt = 0; kt < nkt; kt += kUnroll) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < kUnroll; ++u) {
                 const int t = kt + u;
                 const int stn = st == kStagesA - 1 ? 0 : st + 1;
                 const int g = 4 * t;
@@ -377,9 +419,20 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
                     }
                     // all reads of stage st have returned except, possibly, the NH fetches just issued,
                     // which read the next stage
-                    asm volatile("s_waitcnt lgkmcnt(%0)\n\ts_barrier" ::"n"(NH) : "memory");
-                    store_a(ra[(u + 1) & 1], st);  // tokens of step t+3
-                    load_a(ra[(u + 1) & 1], min(t + 5, last));
+                    if constexpr (kDmaA) {
+                        // This wavefront's copies of step t+2 were issued two steps ago, after the
+                        // barrier of step t-2 (for t < 2: in the prologue); since then it has issued
+                        // the kNP copies of step t+3 and at least 16 weight-fragment loads (2 in the
+                        // rest of that slice, 8 in step t-1, 6 in this step), so vmcnt(16) leaves them
+                        // landed: after the barrier every wavefront may read step t+2, whose first
+                        // fragments are fetched before the next barrier.
+                        asm volatile("s_waitcnt vmcnt(16) lgkmcnt(%0)\n\ts_barrier" ::"n"(NH) : "memory");
+                        copy_a(st, min(t + 4, last));  // tokens of step t+4; past the end: a harmless reload
+                    } else {
+                        asm volatile("s_waitcnt lgkmcnt(%0)\n\ts_barrier" ::"n"(NH) : "memory");
+                        store_a(ra[(u + 1) & 1], st);  // tokens of step t+3
+                        load_a(ra[(u + 1) & 1], min(t + 5, last));
+                    }
 #pragma unroll
                     for (int j = NH; j < NJ; ++j) mma_roll(j, fb, next);
                     load_bf(fb, g + kBAhead + 3);
@@ -389,7 +442,7 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
                             __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
                             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                         }
-                        if (q < kNP) {
+                        if (!kDmaA && q < kNP) {
                             __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
                             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                         }
@@ -399,6 +452,8 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
                 st = stn;
             }
         }
+        // no copy may still be on its way into LDS when the epilogue reuses it or the workgroup ends
+        if constexpr (kDmaA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
     switch (max(0, min(kNJ, (cnt + 31) / 32 - wm * kNJ))) {  // uniform over the wavefront
         case 8: if constexpr (kNJ >= 8) run(std::integral_constant<int, 8>{}); break;
