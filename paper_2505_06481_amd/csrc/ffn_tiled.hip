@@ -14,9 +14,12 @@
 //
 // Memory pipeline: the pool is stored as matrix-core fragments, so a wavefront loads its
 // weight operands straight from global memory into registers (16 bytes per lane, 1 KB per
-// instruction, contiguous), two steps ahead of their use.  Token rows go global -> registers
-// -> a three-stage ring of LDS tiles, [row][64 k] bf16 (128 bytes a row) with the 16-byte
-// pieces xor-swizzled by (row >> 1) & 7, and are read back as fragments; one barrier per step.
+// instruction, contiguous), four steps ahead of their use.  Token rows are copied global ->
+// LDS without passing registers (global_load_lds, 16 bytes per lane) into a four-stage ring
+// of LDS tiles, [row][64 k] bf16 (128 bytes a row) with the 16-byte pieces xor-swizzled by
+// (row >> 1) & 7, two steps ahead, and are read back as fragments; one barrier per step.
+// MMOE_TILED_DMA=0 builds the earlier variant that stages token rows through registers
+// (three-stage ring, weights two steps ahead).
 //
 // Ragged groups: row ranges come from the device array `offsets`.  A one-workgroup
 // preparation kernel turns them into lists of tiles; the product kernels map their
@@ -36,16 +39,12 @@ enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2 };
 constexpr int kBM = 256;  // token rows per tile
 constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
-#ifndef MMOE_TILED_WM
-#define MMOE_TILED_WM 1
-#endif
 #ifndef MMOE_TILED_DMA
 #define MMOE_TILED_DMA 1
 #endif
 #ifndef MMOE_TILED_BAHEAD
-#define MMOE_TILED_BAHEAD (MMOE_TILED_WM == 1 ? (MMOE_TILED_DMA ? 16 : 8) : 4)
+#define MMOE_TILED_BAHEAD (MMOE_TILED_DMA ? 16 : 8)
 #endif
-constexpr int kTiledWM = MMOE_TILED_WM;  // wavefronts along the token rows: 1 = four wavefronts, 2 = eight
 constexpr int kXcds = 8;
 constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB: one step of the token operand
 constexpr bool kDmaA = MMOE_TILED_DMA;     // token rows: global -> LDS copies without staging registers
@@ -182,13 +181,8 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
     }
 }
 
-// WM = wavefronts along the token rows.  1: four wavefronts (one per SIMD), each with all 256
-// token rows and 64 weight rows.  2: eight wavefronts (two per SIMD, so that one can issue
-// matrix instructions while the other is held up issuing loads or LDS writes), each with 128
-// token rows and 64 weight rows; the two wavefronts with the same weight rows load the same
-// weight fragments (the second load hits in the compute unit's L1).
-template <int MODE, int WM>
-__global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __restrict__ A,
+template <int MODE>
+__global__ __launch_bounds__(256, 1) void tiled_kernel(const uint16_t* __restrict__ A,
                                                             const int32_t* __restrict__ tab, int list_hi,
                                                             int list_lo, const uint16_t* __restrict__ W0,
                                                             const uint16_t* __restrict__ W1,
@@ -216,17 +210,16 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
     const int n0 = nt * kFeat;
 
     constexpr int NB = 2;             // 32-row weight blocks per wavefront
-    constexpr int kWaves = 4 * WM;
+    constexpr int kWaves = 4;         // one per SIMD
     constexpr int kThreads = kWaves * 64;
-    constexpr int kNJ = 8 / WM;       // 32-row token sub-tiles per wavefront
+    constexpr int kNJ = 8;            // 32-row token sub-tiles per wavefront (all rows of the tile)
     constexpr int kBAhead = MMOE_TILED_BAHEAD;  // 16-k slices between a weight fragment's load and its use (4 or 8)
     constexpr int kNP = 2048 / kThreads;  // 16-byte pieces of a token tile per thread
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps bases in scalar registers
     const int lr = lane & 31;
-    const int wn = wave & 3;          // which 64 weight rows of the tile
-    const int wm = wave >> 2;         // which kNJ token sub-tiles of the tile
+    const int wn = wave;              // which 64 weight rows of the tile
 
     // ---- token operand: global -> registers -> LDS ----------------------------------------------
     // Piece id = i*kThreads + tid (i < kNP) of a [256 rows][8 pieces of 16 bytes] tile: 8
@@ -299,7 +292,7 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
     int frag_off[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-        frag_off[kk] = (wm * kNJ * 32 + lr) * 128 + ((((lane >> 5) * 4 + kk) ^ ((lr >> 1) & 7)) << 4);
+        frag_off[kk] = lr * 128 + ((((lane >> 5) * 4 + kk) ^ ((lr >> 1) & 7)) << 4);
 
     f32x16 acc[kNJ][NB];  // [token sub-tile][weight block]
 #pragma unroll
@@ -310,21 +303,22 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
             for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
 
     // Main loop, instantiated for NJ = number of this wavefront's 32-row token sub-tiles that
-    // hold rows (all kNJ for every tile but the last one of a slot; a wavefront with none still
-    // stages tokens and meets the barriers).
+    // hold rows (all 8 for every tile but the last one of a slot).
     //
-    // Pipeline (k step t = 64 k = four 16-k slices; step t's tokens live in LDS stage t mod 3):
-    //   weights   slice g is loaded straight into registers 8 slices (two steps) before use;
-    //   tokens    step t is loaded into registers during step t-5 and written to its LDS stage
-    //             during step t-3, so a load has two steps to arrive; token fragments roll
-    //             through one set of registers: as soon as the two matrix instructions that use
-    //             fragment j have been issued, fragment j of the next slice is fetched into it;
+    // Pipeline (k step t = 64 k = four 16-k slices; step t's tokens live in LDS stage t mod 4):
+    //   weights   slice g is loaded straight into registers kBAhead slices (four steps) before
+    //             use; these are ordinary loads and the compiler inserts their waits;
+    //   tokens    the copies of step t+4 are issued right after the barrier of step t, into the
+    //             stage that step t has just finished with, and must have landed by the barrier
+    //             of step t+2; token fragments roll through one set of registers: as soon as the
+    //             two matrix instructions that use fragment j have been issued, fragment j of
+    //             the next slice is fetched into it;
     //   barrier   one per step, in the middle of its last slice: by then every wavefront's
     //             reads of the step's stage have returned (only the first NJ/2 fetches of the
-    //             next stage may be in flight), so nobody waits for LDS, and the stage can take
-    //             the tokens of step t+3.
-    // Every load is an ordinary load, so the compiler inserts exact waits; the loop is unrolled by
-    // two steps so that the rings of registers are indexed statically.
+    //             next stage may be in flight), so nobody waits for LDS.
+    // The loop is unrolled by kBAhead/4 steps so that the ring of weight registers is indexed
+    // statically.  (Register-staged variant: tokens of step t are loaded during step t-5 and
+    // written to stage t mod 3 during step t-3.)
     const int nkt = K / kBK;         // even: K is a multiple of 256
     const int last = nkt - 1;
     const int last_slice = K / 16 - 1;
@@ -334,7 +328,7 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
         struct BFrags {
             u32x4 b[NB];
         };
-        bf16x8 fa[NJ > 0 ? NJ : 1];
+        bf16x8 fa[NJ];
         auto frag_ptr = [&](int stage, int kk) { return lds_a + stage * kTileBytes + frag_off[kk]; };
         auto load_bf = [&](BFrags& fr, int g) {
             const size_t o = (size_t)min(g, last_slice) * 1024;  // past the end: a harmless reload
@@ -455,16 +449,15 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
         // no copy may still be on its way into LDS when the epilogue reuses it or the workgroup ends
         if constexpr (kDmaA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
-    switch (max(0, min(kNJ, (cnt + 31) / 32 - wm * kNJ))) {  // uniform over the wavefront
-        case 8: if constexpr (kNJ >= 8) run(std::integral_constant<int, 8>{}); break;
-        case 7: if constexpr (kNJ >= 8) run(std::integral_constant<int, 7>{}); break;
-        case 6: if constexpr (kNJ >= 8) run(std::integral_constant<int, 6>{}); break;
-        case 5: if constexpr (kNJ >= 8) run(std::integral_constant<int, 5>{}); break;
+    switch (min(kNJ, (cnt + 31) / 32)) {  // uniform over the workgroup
+        case 8: run(std::integral_constant<int, 8>{}); break;
+        case 7: run(std::integral_constant<int, 7>{}); break;
+        case 6: run(std::integral_constant<int, 6>{}); break;
+        case 5: run(std::integral_constant<int, 5>{}); break;
         case 4: run(std::integral_constant<int, 4>{}); break;
         case 3: run(std::integral_constant<int, 3>{}); break;
         case 2: run(std::integral_constant<int, 2>{}); break;
-        case 1: run(std::integral_constant<int, 1>{}); break;
-        default: if constexpr (WM > 1) run(std::integral_constant<int, 0>{}); break;
+        default: run(std::integral_constant<int, 1>{}); break;
     }
 
     // ---- epilogue -------------------------------------------------------------------------------
@@ -480,10 +473,10 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
     constexpr int kRpi = 64 / kLpr;                   // rows per read-back instruction
     constexpr int kChunks = MODE == kTModeSwigluH ? 1 : NB;       // 32-feature chunks this wavefront stores
     const int wfeat = MODE == kTModeSwigluH ? wn * 32 : wn * 64;
-    const int wrow = wm * kNJ * 32;                   // first tile row of this wavefront
-    __shared__ __attribute__((aligned(16))) char lds_epi[kWaves][32 * (32 * 4 + 16)];
-    char* ebuf = lds_epi[wave];
-    char* const obase = reinterpret_cast<char*>(out) + ((size_t)(r0 + wrow) * N + n0 + wfeat) * kEsz +
+    // the patches reuse the token ring: every wavefront has left the main loop
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    char* ebuf = lds_a + wave * (32 * (32 * 4 + 16));
+    char* const obase = reinterpret_cast<char*>(out) + ((size_t)r0 * N + n0 + wfeat) * kEsz +
                         (size_t)(lane / kLpr) * N * kEsz + (lane % kLpr) * 16;
     // o[4q + e]: the 16 finished values of this lane for token sub-tile j, feature chunk c
     auto emit = [&](int j, int c, const float (&o)[16]) {
@@ -503,13 +496,13 @@ __global__ __launch_bounds__(256 * WM, 1) void tiled_kernel(const uint16_t* __re
         for (int it = 0; it < 32 / kRpi; ++it) {
             const int row = it * kRpi + lane / kLpr;
             const u32x4 v = *reinterpret_cast<const u32x4*>(ebuf + row * kPitch + (lane % kLpr) * 16);
-            if (wrow + j * 32 + row < cnt)
+            if (j * 32 + row < cnt)
                 *reinterpret_cast<u32x4*>(obase + ((size_t)(j * 32 + it * kRpi) * N + c * 32) * kEsz) = v;
         }
     };
 #pragma unroll
     for (int j = 0; j < kNJ; ++j) {
-        if (wrow + j * 32 >= cnt) break;  // uniform over the wavefront
+        if (j * 32 >= cnt) break;  // uniform over the workgroup
 #pragma unroll
         for (int c = 0; c < kChunks; ++c) {
             float o[16];
@@ -547,19 +540,19 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets
     int nt_up, nt_down;
     tiled_nts(s, nt_up, nt_down);
     const TileLists L = tile_lists(P, s.S, nt_up, nt_down);
-    dim3 block(256 * kTiledWM);
+    dim3 block(256);
     const uint16_t* nul = nullptr;
     hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, L);
     if (s.act == MMOE_SWIGLU)
-        hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH, kTiledWM>), dim3(L.cap[0] * kXcds), block, 0, st,
+        hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH>), dim3(L.cap[0] * kXcds), block, 0, st,
                            (const uint16_t*)Xg, tab, L.list[0][0], L.list[0][1], (const uint16_t*)W1p,
                            (const uint16_t*)W3p, H, d, f, nt_up);
     else
-        hipLaunchKernelGGL((tiled_kernel<kTModeReluH, kTiledWM>), dim3(L.cap[0] * kXcds), block, 0, st,
+        hipLaunchKernelGGL((tiled_kernel<kTModeReluH>), dim3(L.cap[0] * kXcds), block, 0, st,
                            (const uint16_t*)Xg, tab, L.list[0][0], L.list[0][1], (const uint16_t*)W1p, nul, H, d, f,
                            nt_up);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    hipLaunchKernelGGL((tiled_kernel<kTModePlainF32, kTiledWM>), dim3(L.cap[1] * kXcds), block, 0, st,
+    hipLaunchKernelGGL((tiled_kernel<kTModePlainF32>), dim3(L.cap[1] * kXcds), block, 0, st,
                        (const uint16_t*)H, tab, L.list[1][0], L.list[1][1], (const uint16_t*)W2p, nul, (void*)Yg, f, d,
                        nt_down);
     return launch_status();
