@@ -50,6 +50,10 @@ constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB: one step of the token opera
 constexpr bool kDmaA = MMOE_TILED_DMA;     // token rows: global -> LDS copies without staging registers
 constexpr int kStagesA = kDmaA ? 4 : 3;    // LDS ring of token tiles
 constexpr int kLongestFirstBelow = 8 * 256;  // tiles of a product: below this, partial tiles go last
+#ifndef MMOE_TILED_NTGROUP
+#define MMOE_TILED_NTGROUP 4
+#endif
+constexpr int kNtGroup = MMOE_TILED_NTGROUP;  // feature tiles whose workgroups start back to back on the same token panel
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -68,8 +72,10 @@ __device__ __forceinline__ float silu_mul_t(float g, float u)
 //   one per (product, feature tiles per XCD): a product with NT feature tiles gives XCD x
 //   the tiles nt with nt mod 8 == x, that is ceil or floor of NT/8 of them; list entry
 //   `local` is the tile that the workgroup with id 8*local + x computes.  A product with many
-//   tiles per compute unit lists them in the order (slot, feature tile, row tile), row tile
-//   fastest.  Workgroups start in id order as compute units become free, so a product with
+//   tiles per compute unit lists them in the order (slot, group of kNtGroup feature tiles, row
+//   tile, feature tile within the group): workgroups start in id order a few microseconds
+//   apart, so the ones that share a token panel and the ones that share a weight panel both
+//   run close enough in time to find the panel in L2.  Workgroups start in id order as compute units become free, so a product with
 //   few tiles per compute unit (fewer than kLongestFirstBelow tiles in all) lists the longest
 //   work first: every full 256-row tile in that order, and after them the partial last tiles
 //   of the slots, those with the most rows first, so that the short ones fill the end of the
@@ -157,7 +163,10 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
                     }
                     const int s = lo, mt_s = base_all[s + 1] - base_all[s];
                     const int rem = e - base_all[s] * nt_x;
-                    const int ntl = rem / mt_s, mi = rem % mt_s;
+                    // groups of kNtGroup feature tiles; inside a group the feature tile runs fastest
+                    const int grp = rem / (kNtGroup * mt_s), within = rem % (kNtGroup * mt_s);
+                    const int g_sz = min(kNtGroup, nt_x - grp * kNtGroup);
+                    const int mi = within / g_sz, ntl = grp * kNtGroup + within % g_sz;
                     ent = make_int4(s, ntl, offsets[s] + mi * kBM, min(kBM, cnt_s[s] - mi * kBM));
                 } else if (e < n_full) {
                     int lo = 0, hi = S;  // largest s with base[s]*nt_x <= e (slots without full tiles have equal bounds)
@@ -167,7 +176,9 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
                     }
                     const int s = lo, mt_s = base[s + 1] - base[s];
                     const int rem = e - base[s] * nt_x;
-                    const int ntl = rem / mt_s, mi = rem % mt_s;
+                    const int grp = rem / (kNtGroup * mt_s), within = rem % (kNtGroup * mt_s);
+                    const int g_sz = min(kNtGroup, nt_x - grp * kNtGroup);
+                    const int mi = within / g_sz, ntl = grp * kNtGroup + within % g_sz;
                     ent = make_int4(s, ntl, offsets[s] + mi * kBM, kBM);
                 } else {
                     const int q = e - n_full;
