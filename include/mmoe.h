@@ -162,7 +162,9 @@ int mmoe_combine(const mmoe_shape *shape, const float *Yg, const int32_t *inv_pe
 /*
  * The whole layer, R -> M -> G -> F -> C, on one stream with no host
  * synchronisation; intermediates live in `ws`.  Arguments as above; the pool is
- * the PACKED one.  Y [T,d] dtype out.
+ * the PACKED one.  Y [T,d] dtype out.  The gathered copy Xg is not materialised: the
+ * expert stage reads row perm[r] / k of X where the staged call reads row r of Xg; the
+ * result is bit-identical to the staged calls'.
  */
 int mmoe_layer_forward(const mmoe_shape *shape, const void *X, const int32_t *vid, const void *Wr,
                        const float *br, const int32_t *M, const void *W1p, const void *W3p,

@@ -51,6 +51,7 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f +
 
 template <typename T, int NW, int KU, int MODE>
 __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict__ A,
+                                                            const int32_t* __restrict__ perm, int kdiv,
                                                             const int32_t* __restrict__ offsets,
                                                             const T* __restrict__ W0, const T* __restrict__ W1,
                                                             void* __restrict__ out, int K, int N)
@@ -80,7 +81,8 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
 #pragma unroll
         for (int mb = 0; mb < kSkMB; ++mb) {
             int rr = min(pass0 + mb * 16 + li, cnt - 1);  // rows past the end re-read the last one; never stored
-            arow[mb] = A + (size_t)(r0 + rr) * K + g * (4 * EPB);
+            const int r = perm ? perm[r0 + rr] / kdiv : r0 + rr;  // gather folded into the loads
+            arow[mb] = A + (size_t)r * K + g * (4 * EPB);
         }
         f32x4 acc[kSkMB][NW];
 #pragma unroll
@@ -192,6 +194,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
 // to it.  Partial sums of the four wavefronts meet in LDS.
 template <int NW, int KU, int MODE>
 __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t* __restrict__ A,
+                                                                 const int32_t* __restrict__ perm, int kdiv,
                                                                  const int32_t* __restrict__ offsets,
                                                                  const uint16_t* __restrict__ W0,
                                                                  const uint16_t* __restrict__ W1,
@@ -218,7 +221,8 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
 
     for (int pass0 = 0; pass0 < cnt; pass0 += 32) {
         const int rr = min(pass0 + tok, cnt - 1);  // tokens past the end re-read the last one; never stored
-        const uint16_t* arow = A + (size_t)(r0 + rr) * K + h * 32;
+        const int r = perm ? perm[r0 + rr] / kdiv : r0 + rr;  // gather folded into the loads
+        const uint16_t* arow = A + (size_t)r * K + h * 32;
         f32x16 acc[NW];
 #pragma unroll
         for (int w = 0; w < NW; ++w)
@@ -310,50 +314,55 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
     }
 }
 
-static int run_skinny_bf16(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                           const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
+static int run_skinny_bf16(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
+                           const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
+                           hipEvent_t mid)
 {
+    const int32_t* noperm = nullptr;
     const int d = s.d_model, f = s.d_ff;
     dim3 block(kSkThreads);
     dim3 g1(f / 32, s.S), g2(d / 32, s.S);
     const uint16_t* nul = nullptr;
     if (s.act == MMOE_SWIGLU)
-        hipLaunchKernelGGL((skinny_frag_kernel<2, 1, kModeSwigluH>), g1, block, 0, st, (const uint16_t*)Xg, offsets,
-                           (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f);
+        hipLaunchKernelGGL((skinny_frag_kernel<2, 1, kModeSwigluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
+                           s.top_k, offsets, (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f);
     else
-        hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeReluH>), g1, block, 0, st, (const uint16_t*)Xg, offsets,
-                           (const uint16_t*)W1p, nul, H, d, f);
+        hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeReluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
+                           s.top_k, offsets, (const uint16_t*)W1p, nul, H, d, f);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModePlainF32>), g2, block, 0, st, (const uint16_t*)H, offsets,
-                       (const uint16_t*)W2p, nul, (void*)Yg, f, d);
+    hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModePlainF32>), g2, block, 0, st, (const uint16_t*)H, noperm, 1,
+                       offsets, (const uint16_t*)W2p, nul, (void*)Yg, f, d);
     return launch_status();
 }
 
 template <typename T>
-static int run_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
+static int run_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
+                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
+                      hipEvent_t mid)
 {
+    const int32_t* noperm = nullptr;
     const int d = s.d_model, f = s.d_ff;
     dim3 block(kSkThreads);
     dim3 g1(f / 16, s.S), g2(d / 16, s.S);
     const T* nul = nullptr;
     if (s.act == MMOE_SWIGLU)
-        hipLaunchKernelGGL((skinny_kernel<T, 2, 1, kModeSwigluH>), g1, block, 0, st, (const T*)Xg, offsets,
-                           (const T*)W1p, (const T*)W3p, H, d, f);
+        hipLaunchKernelGGL((skinny_kernel<T, 2, 1, kModeSwigluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
+                           offsets, (const T*)W1p, (const T*)W3p, H, d, f);
     else
-        hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH>), g1, block, 0, st, (const T*)Xg, offsets,
-                           (const T*)W1p, nul, H, d, f);
+        hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
+                           offsets, (const T*)W1p, nul, H, d, f);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModePlainF32>), g2, block, 0, st, (const T*)H, offsets,
-                       (const T*)W2p, nul, (void*)Yg, f, d);
+    hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModePlainF32>), g2, block, 0, st, (const T*)H, noperm, 1,
+                       offsets, (const T*)W2p, nul, (void*)Yg, f, d);
     return launch_status();
 }
 
-int launch_ffn_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st, hipEvent_t mid)
+int launch_ffn_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
+                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
+                      hipEvent_t mid)
 {
-    if (s.dtype == MMOE_BF16) return run_skinny_bf16(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st, mid);
-    return run_skinny<float>(s, Xg, offsets, W1p, W3p, W2p, H, Yg, st, mid);
+    if (s.dtype == MMOE_BF16) return run_skinny_bf16(s, rows, perm, offsets, W1p, W3p, W2p, H, Yg, st, mid);
+    return run_skinny<float>(s, rows, perm, offsets, W1p, W3p, W2p, H, Yg, st, mid);
 }
 
 }  // namespace mmoe

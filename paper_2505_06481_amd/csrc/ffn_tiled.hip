@@ -75,7 +75,7 @@ __device__ __forceinline__ float silu_mul_t(float g, float u)
 //   tiles per compute unit lists them in the order (slot, group of kNtGroup feature tiles, row
 //   tile, feature tile within the group): workgroups start in id order a few microseconds
 //   apart, so the ones that share a token panel and the ones that share a weight panel both
-//   run close enough in time to find the panel in L2.  Workgroups start in id order as compute units become free, so a product with
+//   run close enough in time to find the panel in L2.  A product with
 //   few tiles per compute unit (fewer than kLongestFirstBelow tiles in all) lists the longest
 //   work first: every full 256-row tile in that order, and after them the partial last tiles
 //   of the slots, those with the most rows first, so that the short ones fill the end of the
@@ -109,11 +109,16 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
                                                          TileLists L)
 {
     __shared__ int cnt_s[kMaxS];       // rows of each slot
+    __shared__ int off_s[kMaxS];       // first row of each slot
     __shared__ int base[kMaxS + 1];    // first full row tile of each slot (prefix sum of count / 256)
     __shared__ int base_all[kMaxS + 1];  // first row tile of each slot, partial tiles included
     __shared__ int ragged[kMaxS];      // slots with a partial last tile, most rows first
     __shared__ int n_ragged;
-    for (int s = threadIdx.x; s < S; s += 256) cnt_s[s] = offsets[s + 1] - offsets[s];
+    for (int s = threadIdx.x; s < S; s += 256) {
+        const int o = offsets[s];
+        off_s[s] = o;
+        cnt_s[s] = offsets[s + 1] - o;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         // counting sort of the partial tiles by occupied 32-row sub-tiles, 8 down to 1
@@ -167,7 +172,7 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
                     const int grp = rem / (kNtGroup * mt_s), within = rem % (kNtGroup * mt_s);
                     const int g_sz = min(kNtGroup, nt_x - grp * kNtGroup);
                     const int mi = within / g_sz, ntl = grp * kNtGroup + within % g_sz;
-                    ent = make_int4(s, ntl, offsets[s] + mi * kBM, min(kBM, cnt_s[s] - mi * kBM));
+                    ent = make_int4(s, ntl, off_s[s] + mi * kBM, min(kBM, cnt_s[s] - mi * kBM));
                 } else if (e < n_full) {
                     int lo = 0, hi = S;  // largest s with base[s]*nt_x <= e (slots without full tiles have equal bounds)
                     while (hi - lo > 1) {
@@ -179,12 +184,12 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
                     const int grp = rem / (kNtGroup * mt_s), within = rem % (kNtGroup * mt_s);
                     const int g_sz = min(kNtGroup, nt_x - grp * kNtGroup);
                     const int mi = within / g_sz, ntl = grp * kNtGroup + within % g_sz;
-                    ent = make_int4(s, ntl, offsets[s] + mi * kBM, kBM);
+                    ent = make_int4(s, ntl, off_s[s] + mi * kBM, kBM);
                 } else {
                     const int q = e - n_full;
                     const int s = ragged[q / nt_x];
                     const int full = cnt_s[s] / kBM;
-                    ent = make_int4(s, q % nt_x, offsets[s] + full * kBM, cnt_s[s] - full * kBM);
+                    ent = make_int4(s, q % nt_x, off_s[s] + full * kBM, cnt_s[s] - full * kBM);
                 }
                 lists[L.list[p][c] + e] = ent;
             }
@@ -194,6 +199,7 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
 
 template <int MODE>
 __global__ __launch_bounds__(256, 1) void tiled_kernel(const uint16_t* __restrict__ A,
+                                                       const int32_t* __restrict__ perm, int kdiv,
                                                             const int32_t* __restrict__ tab, int list_hi,
                                                             int list_lo, const uint16_t* __restrict__ W0,
                                                             const uint16_t* __restrict__ W1,
@@ -236,13 +242,19 @@ __global__ __launch_bounds__(256, 1) void tiled_kernel(const uint16_t* __restric
     // Piece id = i*kThreads + tid (i < kNP) of a [256 rows][8 pieces of 16 bytes] tile: 8
     // consecutive threads read one row's 128 contiguous bytes.  Rows past the end of the group
     // re-read its last row (they are multiplied but never stored).
-    const char* a_base = reinterpret_cast<const char*>(A) + (size_t)r0 * K * 2;
-    uint32_t a_off[kNP];
+    // Grouped row r is row r of A, or, when a permutation is given, row perm[r] / kdiv of A (the
+    // gather of the token rows folded into this product's loads).
+    const char* a_base = reinterpret_cast<const char*>(A);
+    uint32_t a_row[kNP];  // byte offset of the row each piece comes from
 #pragma unroll
     for (int i = 0; i < kNP; ++i) {
         const int row = i * (kThreads / 8) + (tid >> 3);
-        a_off[i] = (uint32_t)min(row, cnt - 1) * (uint32_t)K * 2u + (tid & 7) * 16;
+        const int r = r0 + min(row, cnt - 1);
+        a_row[i] = (uint32_t)(perm ? perm[r] / kdiv : r) * (uint32_t)K * 2u;
     }
+    uint32_t a_off[kNP];
+#pragma unroll
+    for (int i = 0; i < kNP; ++i) a_off[i] = a_row[i] + (tid & 7) * 16;
     // LDS position of piece i: row*128 + swizzled piece; (row >> 1) & 7 does not depend on i, so
     // the positions are one register plus multiples of kThreads*16
     const int a_lds0 = (tid >> 3) * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
@@ -251,10 +263,7 @@ __global__ __launch_bounds__(256, 1) void tiled_kernel(const uint16_t* __restric
     // the lane that fills physical piece q of a row fetches logical piece q ^ ((row >> 1) & 7).
     uint32_t a_goff[kNP];
 #pragma unroll
-    for (int i = 0; i < kNP; ++i) {
-        const int row = i * (kThreads / 8) + (tid >> 3);
-        a_goff[i] = (uint32_t)min(row, cnt - 1) * (uint32_t)K * 2u + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
-    }
+    for (int i = 0; i < kNP; ++i) a_goff[i] = a_row[i] + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
     // The copies are written in assembly so that the compiler's wait-count bookkeeping does not
     // see them (it would drain every load in flight before each LDS read); the waits that order
     // them are written out next to the barriers.  M0 is only used here.
@@ -541,9 +550,9 @@ size_t tiled_table_bytes(const mmoe_shape& s)
     return align256(tile_lists(s.T * s.top_k, s.S, nt_up, nt_down).bytes);
 }
 
-int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                     const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab, hipStream_t st,
-                     hipEvent_t mid)
+int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
+                     const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
+                     hipStream_t st, hipEvent_t mid)
 {
     if (s.dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     const int P = s.T * s.top_k, d = s.d_model, f = s.d_ff;
@@ -556,16 +565,16 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets
     hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, L);
     if (s.act == MMOE_SWIGLU)
         hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH>), dim3(L.cap[0] * kXcds), block, 0, st,
-                           (const uint16_t*)Xg, tab, L.list[0][0], L.list[0][1], (const uint16_t*)W1p,
-                           (const uint16_t*)W3p, H, d, f, nt_up);
+                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
+                           (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, nt_up);
     else
         hipLaunchKernelGGL((tiled_kernel<kTModeReluH>), dim3(L.cap[0] * kXcds), block, 0, st,
-                           (const uint16_t*)Xg, tab, L.list[0][0], L.list[0][1], (const uint16_t*)W1p, nul, H, d, f,
-                           nt_up);
+                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
+                           (const uint16_t*)W1p, nul, H, d, f, nt_up);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
     hipLaunchKernelGGL((tiled_kernel<kTModePlainF32>), dim3(L.cap[1] * kXcds), block, 0, st,
-                       (const uint16_t*)H, tab, L.list[1][0], L.list[1][1], (const uint16_t*)W2p, nul, (void*)Yg, f, d,
-                       nt_down);
+                       (const uint16_t*)H, (const int32_t*)nullptr, 1, tab, L.list[1][0], L.list[1][1],
+                       (const uint16_t*)W2p, nul, (void*)Yg, f, d, nt_down);
     return launch_status();
 }
 

@@ -37,7 +37,6 @@ WsLayout ws_layout(const mmoe_shape& s)
     L.blk_counts = take((size_t)L.nblk * s.S * 4);
     L.blk_base = take((size_t)L.nblk * s.S * 4);
     L.tile_tab = take(tiled_table_bytes(s));
-    L.Xg = take(P * s.d_model * es);
     L.H = take(P * s.d_ff * es);
     L.Yg = take(P * s.d_model * 4);
     L.total = off;
@@ -146,8 +145,9 @@ int mmoe_expert_ffn(const mmoe_shape* shape, const void* Xg, const int32_t* offs
         misaligned(W2p, 16) || misaligned(Yg, 16) || misaligned(offsets, 4))
         return MMOE_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    if (use_skinny(*shape)) return launch_ffn_skinny(*shape, Xg, offsets, W1p, W3p, W2p, ws, Yg, st);
-    return launch_ffn_tiled(*shape, Xg, offsets, W1p, W3p, W2p, ws, Yg, (int32_t*)((char*)ws + h_bytes), st);
+    if (use_skinny(*shape)) return launch_ffn_skinny(*shape, Xg, nullptr, offsets, W1p, W3p, W2p, ws, Yg, st);
+    return launch_ffn_tiled(*shape, Xg, nullptr, offsets, W1p, W3p, W2p, ws, Yg, (int32_t*)((char*)ws + h_bytes),
+                            st);
 }
 
 int mmoe_combine(const mmoe_shape* shape, const float* Yg, const int32_t* inv_perm, const float* topk_w,
@@ -192,15 +192,17 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
     if ((rc = mark(MMOE_EV_START))) return rc;
     if ((rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st))) return rc;
     if ((rc = mark(MMOE_EV_ROUTE))) return rc;
+    // no gathered copy of the token rows: the up product reads X through perm
+    int32_t* perm = (int32_t*)(w + L.perm);
     rc = launch_permute(*shape, X, vid, topk_idx, M, (int32_t*)(w + L.slot), (int32_t*)(w + L.counts), offsets,
-                        (int32_t*)(w + L.perm), inv_perm, w + L.Xg, (int32_t*)(w + L.blk_counts),
-                        (int32_t*)(w + L.blk_base), L.nblk, st);
+                        perm, inv_perm, nullptr, (int32_t*)(w + L.blk_counts), (int32_t*)(w + L.blk_base), L.nblk,
+                        st);
     if (rc) return rc;
     if ((rc = mark(MMOE_EV_PERMUTE))) return rc;
     if (use_skinny(*shape))
-        rc = launch_ffn_skinny(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, st, mid);
+        rc = launch_ffn_skinny(*shape, X, perm, offsets, W1p, W3p, W2p, w + L.H, Yg, st, mid);
     else
-        rc = launch_ffn_tiled(*shape, w + L.Xg, offsets, W1p, W3p, W2p, w + L.H, Yg, (int32_t*)(w + L.tile_tab), st,
+        rc = launch_ffn_tiled(*shape, X, perm, offsets, W1p, W3p, W2p, w + L.H, Yg, (int32_t*)(w + L.tile_tab), st,
                               mid);
     if (rc) return rc;
     if ((rc = mark(MMOE_EV_FFN_DOWN))) return rc;

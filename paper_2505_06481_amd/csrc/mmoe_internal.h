@@ -37,7 +37,7 @@ inline size_t elem_size(int dtype) { return dtype == MMOE_BF16 ? 2 : 4; }
 
 // Sub-buffers of the caller's workspace used by mmoe_layer_forward (byte offsets).
 struct WsLayout {
-    size_t topk_idx, topk_w, slot, counts, offsets, perm, inv_perm, blk_counts, blk_base, tile_tab, Xg, H, Yg, total;
+    size_t topk_idx, topk_w, slot, counts, offsets, perm, inv_perm, blk_counts, blk_base, tile_tab, H, Yg, total;
     int nblk;
 };
 WsLayout ws_layout(const mmoe_shape& s);
@@ -50,19 +50,21 @@ bool use_skinny(const mmoe_shape& s);
 // Kernel launchers (one per translation unit).  All return an mmoe_status.
 int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const void* Wr, const float* br,
                  int32_t* topk_idx, float* topk_w, hipStream_t st);
+// `Xg` null: everything but the row gather (the fused layer reads token rows through `perm`).
 int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const int32_t* topk_idx,
                    const int32_t* M, int32_t* slot, int32_t* counts, int32_t* offsets, int32_t* perm,
                    int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk,
                    hipStream_t st);
-// Expert stage.  `mid`, when not null, is recorded between the up product (+ activation)
-// and the down product.
-int launch_ffn_skinny(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                      const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
+// Expert stage.  Row r of the grouped input is rows[r] when `perm` is null (rows = Xg), and
+// rows[perm[r] / top_k] otherwise (rows = X: the gather is folded into the up product's loads).
+// `mid`, when not null, is recorded between the up product (+ activation) and the down product.
+int launch_ffn_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
+                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
                       hipEvent_t mid = nullptr);
 // `tab`: tiled_table_bytes() of scratch for the row-tile table.
-int launch_ffn_tiled(const mmoe_shape& s, const void* Xg, const int32_t* offsets, const void* W1p,
-                     const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab, hipStream_t st,
-                     hipEvent_t mid = nullptr);
+int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
+                     const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
+                     hipStream_t st, hipEvent_t mid = nullptr);
 size_t tiled_table_bytes(const mmoe_shape& s);
 int launch_combine(const mmoe_shape& s, const float* Yg, const int32_t* inv_perm, const float* topk_w,
                    void* Y, hipStream_t st);

@@ -272,13 +272,14 @@ int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const
         hipLaunchKernelGGL(slot_group_small_kernel, dim3(1), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot, counts,
                            offsets, perm, inv_perm, P, s.top_k, s.V, s.E, s.S);
     else {
-    hipLaunchKernelGGL(slot_hist_kernel, dim3(nblk), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot,
-                       blk_counts, P, s.top_k, s.V, s.E, s.S);
-    hipLaunchKernelGGL(slot_scan_kernel, dim3(1), dim3(kPermThreads), 0, st, blk_counts, blk_base, counts,
-                       offsets, nblk, s.S);
-    hipLaunchKernelGGL(slot_scatter_kernel, dim3(nblk), dim3(kPermThreads), 0, st, slot, blk_base, perm,
-                       inv_perm, P, s.S);
+        hipLaunchKernelGGL(slot_hist_kernel, dim3(nblk), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot,
+                           blk_counts, P, s.top_k, s.V, s.E, s.S);
+        hipLaunchKernelGGL(slot_scan_kernel, dim3(1), dim3(kPermThreads), 0, st, blk_counts, blk_base, counts,
+                           offsets, nblk, s.S);
+        hipLaunchKernelGGL(slot_scatter_kernel, dim3(nblk), dim3(kPermThreads), 0, st, slot, blk_base, perm,
+                           inv_perm, P, s.S);
     }
+    if (!Xg) return launch_status();
     const int row_vec = (int)((size_t)s.d_model * elem_size(s.dtype) / 16);
     hipLaunchKernelGGL(gather_rows_kernel, dim3((P + kPermWaves - 1) / kPermWaves), dim3(kPermThreads), 0, st,
                        (const u32x4*)X, perm, (u32x4*)Xg, P, s.top_k, row_vec);

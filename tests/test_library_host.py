@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(mm):
 def test_workspace_size_accounts_for_every_intermediate(mm):
     sh = mm.make_shape(8192, 4096, 14336, 2, 8, 12, 2, "bf16", "swiglu")
     P = 8192 * 2
-    need = P * 4096 * 2 + P * 14336 * 2 + P * 4096 * 4     # Xg + H + Yg
+    need = P * 14336 * 2 + P * 4096 * 4     # H + Yg (the fused layer keeps no gathered copy of the tokens)
     got = mm.workspace_bytes(sh)
     assert need <= got <= need + (1 << 20)
     assert mm.workspace_bytes(mm.make_shape(8, 100, 256, 1, 1, 1, 1, "f32", "relu")) == 0
