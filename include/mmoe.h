@@ -194,6 +194,17 @@ int mmoe_layer_forward_events(const mmoe_shape *shape, const void *X, const int3
                               void *stream, void *const *events);
 
 /*
+ * Tuning knob, host only, process-wide (not thread-safe against concurrent calls of the
+ * expert stage): the number of token rows per tile of the matrix-core expert kernels.
+ * 0 (the default) chooses by shape: 256 rows when the batch fills the chip several times
+ * over, 128 rows (more, shorter tiles; two workgroups per compute unit) otherwise.  128
+ * or 256 forces that height for every later call.  Either height sums every output
+ * element in the same order, so the results are bit-identical.  Returns 0, or MMOE_ERR_DIM
+ * for any other value.
+ */
+int mmoe_set_expert_tile_rows(int rows);
+
+/*
  * Debugging aid, SYNCHRONISES the stream: checks on the device that every vid[t] is in
  * [0,V) and every M[v][e] in [0,S).  Returns 0 if so, 1 if not, a negative status on
  * argument errors.  `ws` needs 256 bytes.

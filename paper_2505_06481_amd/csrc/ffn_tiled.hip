@@ -36,17 +36,14 @@ namespace mmoe {
 
 enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2 };
 
-constexpr int kBM = 256;  // token rows per tile
+constexpr int kBMBig = 256;    // token rows per tile: large batches (one workgroup per compute unit)
+constexpr int kBMSmall = 128;  // token rows per tile: batches with few tiles (two workgroups per compute unit)
 constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
 #ifndef MMOE_TILED_DMA
 #define MMOE_TILED_DMA 1
 #endif
-#ifndef MMOE_TILED_BAHEAD
-#define MMOE_TILED_BAHEAD (MMOE_TILED_DMA ? 16 : 8)
-#endif
 constexpr int kXcds = 8;
-constexpr int kTileBytes = kBM * kBK * 2;  // 32 KB: one step of the token operand
 constexpr bool kDmaA = MMOE_TILED_DMA;     // token rows: global -> LDS copies without staging registers
 constexpr int kStagesA = kDmaA ? 4 : 3;    // LDS ring of token tiles
 constexpr int kLongestFirstBelow = 8 * 256;  // tiles of a product: below this, partial tiles go last
@@ -87,10 +84,10 @@ struct TileLists {
     size_t bytes;
 };
 
-static TileLists tile_lists(int P, int S, int nt_up, int nt_down)
+static TileLists tile_lists(int P, int S, int nt_up, int nt_down, int bm)
 {
     TileLists L;
-    const int mt = (P + kBM - 1) / kBM + S;  // upper bound of the number of row tiles
+    const int mt = (P + bm - 1) / bm + S;  // upper bound of the number of row tiles
     L.hdr = 0;
     L.cap[0] = mt * ((nt_up + kXcds - 1) / kXcds);
     L.cap[1] = mt * ((nt_down + kXcds - 1) / kXcds);
@@ -106,7 +103,7 @@ static TileLists tile_lists(int P, int S, int nt_up, int nt_down)
 
 __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restrict__ offsets,
                                                          int32_t* __restrict__ tab, int S, int nt_up, int nt_down,
-                                                         TileLists L)
+                                                         int bm, TileLists L)
 {
     __shared__ int cnt_s[kMaxS];       // rows of each slot
     __shared__ int off_s[kMaxS];       // first row of each slot
@@ -127,9 +124,9 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
         for (int s = 0; s < S; ++s) {
             base[s] = run;
             base_all[s] = run_all;
-            run += cnt_s[s] / kBM;
-            run_all += (cnt_s[s] + kBM - 1) / kBM;
-            const int rem = cnt_s[s] % kBM;
+            run += cnt_s[s] / bm;
+            run_all += (cnt_s[s] + bm - 1) / bm;
+            const int rem = cnt_s[s] % bm;
             if (rem) ++bucket[(rem + 31) / 32];
         }
         base[S] = run;
@@ -142,7 +139,7 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
         }
         n_ragged = at;
         for (int s = 0; s < S; ++s) {
-            const int rem = cnt_s[s] % kBM;
+            const int rem = cnt_s[s] % bm;
             if (rem) ragged[bucket[(rem + 31) / 32]++] = s;
         }
         tab[L.hdr] = run + at;
@@ -172,7 +169,7 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
                     const int grp = rem / (kNtGroup * mt_s), within = rem % (kNtGroup * mt_s);
                     const int g_sz = min(kNtGroup, nt_x - grp * kNtGroup);
                     const int mi = within / g_sz, ntl = grp * kNtGroup + within % g_sz;
-                    ent = make_int4(s, ntl, off_s[s] + mi * kBM, min(kBM, cnt_s[s] - mi * kBM));
+                    ent = make_int4(s, ntl, off_s[s] + mi * bm, min(bm, cnt_s[s] - mi * bm));
                 } else if (e < n_full) {
                     int lo = 0, hi = S;  // largest s with base[s]*nt_x <= e (slots without full tiles have equal bounds)
                     while (hi - lo > 1) {
@@ -184,12 +181,12 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
                     const int grp = rem / (kNtGroup * mt_s), within = rem % (kNtGroup * mt_s);
                     const int g_sz = min(kNtGroup, nt_x - grp * kNtGroup);
                     const int mi = within / g_sz, ntl = grp * kNtGroup + within % g_sz;
-                    ent = make_int4(s, ntl, off_s[s] + mi * kBM, kBM);
+                    ent = make_int4(s, ntl, off_s[s] + mi * bm, bm);
                 } else {
                     const int q = e - n_full;
                     const int s = ragged[q / nt_x];
-                    const int full = cnt_s[s] / kBM;
-                    ent = make_int4(s, q % nt_x, off_s[s] + full * kBM, cnt_s[s] - full * kBM);
+                    const int full = cnt_s[s] / bm;
+                    ent = make_int4(s, q % nt_x, off_s[s] + full * bm, cnt_s[s] - full * bm);
                 }
                 lists[L.list[p][c] + e] = ent;
             }
@@ -197,14 +194,15 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
     }
 }
 
-template <int MODE>
-__global__ __launch_bounds__(256, 1) void tiled_kernel(const uint16_t* __restrict__ A,
+template <int MODE, int BM>
+__global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const uint16_t* __restrict__ A,
                                                        const int32_t* __restrict__ perm, int kdiv,
                                                             const int32_t* __restrict__ tab, int list_hi,
                                                             int list_lo, const uint16_t* __restrict__ W0,
                                                             const uint16_t* __restrict__ W1,
                                                             void* __restrict__ out, int K, int N, int NT)
 {
+    constexpr int kTileBytes = BM * kBK * 2;  // one step of the token operand (32 KB for 256 rows)
     __shared__ __attribute__((aligned(1024))) char lds_a[kStagesA * kTileBytes];
 
     // ---- workgroup id -> tile ------------------------------------------------------------
@@ -229,9 +227,10 @@ __global__ __launch_bounds__(256, 1) void tiled_kernel(const uint16_t* __restric
     constexpr int NB = 2;             // 32-row weight blocks per wavefront
     constexpr int kWaves = 4;         // one per SIMD
     constexpr int kThreads = kWaves * 64;
-    constexpr int kNJ = 8;            // 32-row token sub-tiles per wavefront (all rows of the tile)
-    constexpr int kBAhead = MMOE_TILED_BAHEAD;  // 16-k slices between a weight fragment's load and its use (4 or 8)
-    constexpr int kNP = 2048 / kThreads;  // 16-byte pieces of a token tile per thread
+    constexpr int kNJ = BM / 32;      // 32-row token sub-tiles per wavefront (all rows of the tile)
+    // 16-k slices between a weight fragment's load and its use: what the registers allow
+    constexpr int kBAhead = (kDmaA && BM == kBMBig) ? 16 : 8;
+    constexpr int kNP = BM * 8 / kThreads;  // 16-byte pieces of a token tile per thread
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps bases in scalar registers
@@ -470,10 +469,10 @@ __global__ __launch_bounds__(256, 1) void tiled_kernel(const uint16_t* __restric
         if constexpr (kDmaA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
     switch (min(kNJ, (cnt + 31) / 32)) {  // uniform over the workgroup
-        case 8: run(std::integral_constant<int, 8>{}); break;
-        case 7: run(std::integral_constant<int, 7>{}); break;
-        case 6: run(std::integral_constant<int, 6>{}); break;
-        case 5: run(std::integral_constant<int, 5>{}); break;
+        case 8: if constexpr (kNJ >= 8) run(std::integral_constant<int, 8>{}); break;
+        case 7: if constexpr (kNJ >= 8) run(std::integral_constant<int, 7>{}); break;
+        case 6: if constexpr (kNJ >= 8) run(std::integral_constant<int, 6>{}); break;
+        case 5: if constexpr (kNJ >= 8) run(std::integral_constant<int, 5>{}); break;
         case 4: run(std::integral_constant<int, 4>{}); break;
         case 3: run(std::integral_constant<int, 3>{}); break;
         case 2: run(std::integral_constant<int, 2>{}); break;
@@ -543,11 +542,55 @@ static void tiled_nts(const mmoe_shape& s, int& nt_up, int& nt_down)
     nt_down = s.d_model / kBN;
 }
 
+// Tile height: 256 rows when the batch fills the chip several times over; 128 rows (two
+// workgroups per compute unit, more and shorter tiles) when the down product, which has the
+// fewest tiles, would otherwise leave compute units idle.  The host knows P and S, not the
+// counts: a slot is taken to end in half a tile.
+static int g_tile_rows = 0;  // 0: by shape; 128 or 256: forced (mmoe_set_expert_tile_rows)
+
+int set_tile_rows(int rows)
+{
+    if (rows != 0 && rows != kBMSmall && rows != kBMBig) return MMOE_ERR_DIM;
+    g_tile_rows = rows;
+    return MMOE_OK;
+}
+
+static int tile_rows(const mmoe_shape& s, int nt_down)
+{
+    if (g_tile_rows) return g_tile_rows;
+    const int64_t P = (int64_t)s.T * s.top_k;
+    const int64_t tiles = (P / kBMBig + (s.S + 1) / 2) * nt_down;
+    return tiles < 2 * 256 ? kBMSmall : kBMBig;
+}
+
 size_t tiled_table_bytes(const mmoe_shape& s)
 {
     int nt_up, nt_down;
     tiled_nts(s, nt_up, nt_down);
-    return align256(tile_lists(s.T * s.top_k, s.S, nt_up, nt_down).bytes);
+    return align256(tile_lists(s.T * s.top_k, s.S, nt_up, nt_down, kBMSmall).bytes);  // the larger of the two
+}
+
+template <int BM>
+static void launch_tiled_products(const mmoe_shape& s, const TileLists& L, const void* rows, const int32_t* perm,
+                                  const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg,
+                                  const int32_t* tab, int nt_up, int nt_down, hipStream_t st, hipEvent_t mid,
+                                  bool& event_failed)
+{
+    const int d = s.d_model, f = s.d_ff;
+    dim3 block(256);
+    const uint16_t* nul = nullptr;
+    if (s.act == MMOE_SWIGLU)
+        hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH, BM>), dim3(L.cap[0] * kXcds), block, 0, st,
+                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
+                           (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, nt_up);
+    else
+        hipLaunchKernelGGL((tiled_kernel<kTModeReluH, BM>), dim3(L.cap[0] * kXcds), block, 0, st,
+                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
+                           (const uint16_t*)W1p, nul, H, d, f, nt_up);
+    if (mid && hipEventRecord(mid, st) != hipSuccess) event_failed = true;
+    hipLaunchKernelGGL((tiled_kernel<kTModePlainF32, BM>), dim3(L.cap[1] * kXcds), block, 0, st,
+                       (const uint16_t*)H, (const int32_t*)nullptr, 1, tab, L.list[1][0], L.list[1][1],
+                       (const uint16_t*)W2p, nul, (void*)Yg, f, d, nt_down);
 }
 
 int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
@@ -559,22 +602,17 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
     if ((int64_t)P * (d > f ? d : f) >= ((int64_t)1 << 31)) return MMOE_ERR_LIMIT;  // 32-bit byte offsets inside a panel
     int nt_up, nt_down;
     tiled_nts(s, nt_up, nt_down);
-    const TileLists L = tile_lists(P, s.S, nt_up, nt_down);
-    dim3 block(256);
-    const uint16_t* nul = nullptr;
-    hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, L);
-    if (s.act == MMOE_SWIGLU)
-        hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH>), dim3(L.cap[0] * kXcds), block, 0, st,
-                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
-                           (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, nt_up);
+    const int bm = tile_rows(s, nt_down);
+    const TileLists L = tile_lists(P, s.S, nt_up, nt_down, bm);
+    hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, bm, L);
+    bool event_failed = false;
+    if (bm == kBMBig)
+        launch_tiled_products<kBMBig>(s, L, rows, perm, W1p, W3p, W2p, H, Yg, tab, nt_up, nt_down, st, mid,
+                                      event_failed);
     else
-        hipLaunchKernelGGL((tiled_kernel<kTModeReluH>), dim3(L.cap[0] * kXcds), block, 0, st,
-                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
-                           (const uint16_t*)W1p, nul, H, d, f, nt_up);
-    if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    hipLaunchKernelGGL((tiled_kernel<kTModePlainF32>), dim3(L.cap[1] * kXcds), block, 0, st,
-                       (const uint16_t*)H, (const int32_t*)nullptr, 1, tab, L.list[1][0], L.list[1][1],
-                       (const uint16_t*)W2p, nul, (void*)Yg, f, d, nt_down);
+        launch_tiled_products<kBMSmall>(s, L, rows, perm, W1p, W3p, W2p, H, Yg, tab, nt_up, nt_down, st, mid,
+                                        event_failed);
+    if (event_failed) return MMOE_ERR_LAUNCH;
     return launch_status();
 }
 

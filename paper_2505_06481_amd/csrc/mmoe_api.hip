@@ -217,6 +217,8 @@ int mmoe_layer_forward(const mmoe_shape* shape, const void* X, const int32_t* vi
     return mmoe_layer_forward_events(shape, X, vid, Wr, br, M, W1p, W3p, W2p, Y, ws, ws_bytes, stream, nullptr);
 }
 
+int mmoe_set_expert_tile_rows(int rows) { return mmoe::set_tile_rows(rows); }
+
 int mmoe_validate_inputs(const mmoe_shape* shape, const int32_t* vid, const int32_t* M, void* ws,
                          size_t ws_bytes, void* stream)
 {

@@ -66,6 +66,7 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
                      hipStream_t st, hipEvent_t mid = nullptr);
 size_t tiled_table_bytes(const mmoe_shape& s);
+int set_tile_rows(int rows);
 int launch_combine(const mmoe_shape& s, const float* Yg, const int32_t* inv_perm, const float* topk_w,
                    void* Y, hipStream_t st);
 int launch_pack(const mmoe_shape& s, const void* W1, const void* W3, const void* W2, void* W1p, void* W3p,

@@ -26,7 +26,7 @@ _TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
 EXPORTS = [
     "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
     "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_layer_forward_events",
-    "mmoe_validate_inputs",
+    "mmoe_validate_inputs", "mmoe_set_expert_tile_rows",
 ]
 
 
@@ -210,3 +210,8 @@ def validate_inputs(shape: Shape, vid, M, ws) -> bool:
     if rc < 0:
         raise MmoeError(rc, "mmoe_validate_inputs")
     return rc == 0
+
+
+def set_expert_tile_rows(rows: int) -> None:
+    """Tuning knob of the matrix-core expert kernels: 0 = by shape, 128 or 256 = forced."""
+    _check(lib().mmoe_set_expert_tile_rows(int(rows)), "mmoe_set_expert_tile_rows")

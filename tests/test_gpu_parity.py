@@ -91,6 +91,18 @@ def test_small_cases_every_stage(mm, gc, oracle, cfg):
     staged_vs_oracle(mm, gc, oracle, cfg)
 
 
+@pytest.mark.parametrize("rows", [256, 128])
+@pytest.mark.parametrize("cfg", [c for c in SMALL if c.name.startswith("t_")], ids=lambda c: c.name)
+def test_both_tile_heights(mm, gc, oracle, cfg, rows):
+    """The matrix-core kernels at a forced tile height (by shape these small batches would only
+    ever get the 128-row tiles): every stage against the oracle, ragged last tiles of 1..8 sub-tiles."""
+    mm.set_expert_tile_rows(rows)
+    try:
+        staged_vs_oracle(mm, gc, oracle, cfg)
+    finally:
+        mm.set_expert_tile_rows(0)
+
+
 def test_edge_cases(mm, gc, oracle):
     # a single token
     staged_vs_oracle(mm, gc, oracle, synth.Config("one_token", 1, 256, 256, 2, 4, 2, "bf16", "swiglu", seed=10))

@@ -81,3 +81,12 @@ def test_binding_refuses_host_tensors(mm):
     sh = mm.make_shape(4, 256, 256, 1, 2, 2, 1, "f32", "relu")
     with pytest.raises(ValueError):
         mm.route(sh, torch.zeros(4, 256), torch.zeros(4, dtype=torch.int32), torch.zeros(1, 2, 256))
+
+
+def test_tile_rows_knob_accepts_only_its_three_values(mm):
+    L = mm.lib()
+    for good in (128, 256, 0):
+        assert L.mmoe_set_expert_tile_rows(good) == 0
+    for bad in (64, 512, -1, 100):
+        assert L.mmoe_set_expert_tile_rows(bad) == -2
+    assert L.mmoe_set_expert_tile_rows(0) == 0
