@@ -32,12 +32,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).  The figures belong
 # to one version of the kernel source; with any other version `traffic` is null.
 TRAFFIC = {
-    "ffn_tiled.hip": {"sha256": "02b68d636d0cd5a7d3c25c8595b5a4e8a6311d884731a5809199b730d254f0d9",
+    "ffn_tiled.hip": {"sha256": "ce2adf846015648b2712c9dc6dc80f54fa58dc8917d8cb13cc63099cb9a58258",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 16391035743, "write_bytes": 469762368},
-    "ffn_skinny.hip": {"sha256": "e67458f5e2cf478f5c1eecbec87ef2a2e36c5761f25073eda6488f37da5e4955",
+                      "fetch_bytes": 13634547830, "write_bytes": 469762736},
+    "ffn_skinny.hip": {"sha256": "9105a3530f258518f599cef4194389f5c9a3547f3d2f3e1badbebe3f9da3ba4d",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3067862950, "write_bytes": 3670800},
+                       "fetch_bytes": 3067220995, "write_bytes": 3670830},
 }
 
 
