@@ -139,12 +139,14 @@ def run_workload(cfg, inp, pool, steps, warmup):
     events.destroy()
     names = ["route", "permute", "ffn_up", "ffn_down", "combine"]
     stages = {n: float(stage_ms[:, j].mean()) for j, n in enumerate(names)}
+    per_step = stage_ms.sum(axis=1)   # first kernel's start to last kernel's end, per step (HIP events)
 
     # per-slot row counts of this batch (for the byte/flop accounting of the roofline)
     sl = mmoe.remap_permute(shape, X, vid, mmoe.route(shape, X, vid, Wr, br)[0], M, ws)
     counts = sl[1].cpu().numpy()
     torch.cuda.synchronize()
-    return dict(ms_per_step=wall / steps * 1e3, stages_ms=stages, counts=counts, S=S, Y=Y)
+    return dict(ms_per_step=wall / steps * 1e3, stages_ms=stages, counts=counts, S=S, Y=Y,
+                events_ms={"median": float(np.median(per_step)), "min": float(per_step.min())})
 
 
 def roofline(cfg, res, skinny):
@@ -247,6 +249,7 @@ def main():
                    "slot_rows": [int(c) for c in res["counts"]]},
         "layer_tflops": layer_flops / (ms * 1e-3) / 1e12,
         "stages_ms": res["stages_ms"],
+        "step_ms_by_events": res["events_ms"],
         "roofline": roofline(cfg, res, skinny),
     }
 
@@ -261,7 +264,7 @@ def main():
             "config": {"workload": dcfg.name, "T": dcfg.T, "S": S, "active_slots": active},
             "value": dcfg.T / (dms * 1e-3), "unit": "tokens/s", "ms_per_step": dms,
             "layer_gbs": active * 3 * dcfg.d_model * dcfg.d_ff * 2 / (dms * 1e-3) / 1e9,
-            "stages_ms": dres["stages_ms"],
+            "stages_ms": dres["stages_ms"], "step_ms_by_events": dres["events_ms"],
             "roofline": roofline(dcfg, dres, True),
         }
 
