@@ -210,3 +210,61 @@ def test_benchmark_shapes_sampled_parity(mm, gc, oracle, name):
     print(f"expert oracle on {len(toks)} sampled tokens", flush=True)
     Y_ref = oracle.layer_tokens(inp, cfg.top_k, cfg.dtype, cfg.act, toks, routed=(idx_ref, w_ref, slot_ref))
     gc.assert_close(gc.to_np64(Y[toks]), Y_ref, cfg.dtype, "Y (sampled)")
+
+
+def test_limits_many_slots_and_widest_router(mm, gc, oracle):
+    """Close to the documented limits: a pool of several hundred slots (most of them empty or
+    nearly empty for a small batch), and E = 256 experts with k = 8."""
+    cfg = synth.Config("many_slots", 300, 256, 256, 64, 16, 2, "bf16", "swiglu", seed=20, share_prob=0.1)
+    case, ref = staged_vs_oracle(mm, gc, oracle, cfg)
+    assert 800 < case.S <= 1024 and (ref["counts"] == 0).any()
+    cfg = synth.Config("many_slots_f32", 90, 256, 256, 40, 16, 1, "f32", "relu", seed=21, share_prob=0.2)
+    staged_vs_oracle(mm, gc, oracle, cfg)
+    staged_vs_oracle(mm, gc, oracle, synth.Config("widest_e", 70, 512, 256, 1, 256, 8, "bf16", "relu", seed=22))
+    # many slots and enough rows for the matrix-core kernels (hundreds of short tile lists)
+    cfg = synth.Config("many_slots_tiled", 6000, 256, 256, 8, 16, 2, "bf16", "swiglu", seed=23, share_prob=0.3)
+    case, ref = staged_vs_oracle(mm, gc, oracle, cfg)
+    assert case.S > 80
+
+
+@pytest.mark.parametrize("name", ["switch8_fp32_v2_t128", "switch8_bf16_v4_t4096", "mixtral_decode_bf16_v2_t64"])
+def test_benchmark_shapes_second_seed(mm, gc, oracle, name):
+    """Robustness row: the same shapes with another seed (another table, other counts)."""
+    staged_vs_oracle(mm, gc, oracle, synth.CONFIGS[name].replace(seed=1))
+
+
+def test_layer_forward_in_a_captured_graph(mm, gc, oracle):
+    """The fused entry point allocates nothing and never synchronises, so a caller can record
+    it into a HIP graph.  Every replay, with new tokens written into the same buffers in
+    between and eager work around it, must reproduce the eager result bit for bit."""
+    for cfg in (synth.Config("graph_stream", 48, 512, 768, 2, 4, 2, "bf16", "swiglu", seed=24),
+                synth.Config("graph_tiled", 800, 256, 512, 2, 4, 2, "bf16", "swiglu", seed=25)):
+        case = gc.DeviceCase(cfg)
+        sh = case.shape
+        Y = torch.empty((cfg.T, cfg.d_model), dtype=case.X.dtype, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):    # warm-up on the capture stream, as graph capture requires
+            mm.layer_forward(sh, case.X, case.vid, case.Wr, case.br, case.M, case.W1p, case.W3p, case.W2p,
+                             case.ws, Y=Y)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            mm.layer_forward(sh, case.X, case.vid, case.Wr, case.br, case.M, case.W1p, case.W3p, case.W2p,
+                             case.ws, Y=Y)
+        for rep in range(3):
+            inp = synth.make_inputs(cfg.replace(seed=100 + rep), weights=False)
+            case.X.copy_(gc.to_dev(inp["X"], cfg.dtype))
+            case.vid.copy_(torch.from_numpy(inp["vid"]).cuda())
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = Y.clone()
+            eager = case.forward()
+            torch.cuda.synchronize()
+            assert torch.equal(got, eager), f"{cfg.name}: replay {rep} differs from the eager result"
+        # and against the oracle once, for the last batch (same pool and table, new tokens)
+        last = dict(case.inp, X=inp["X"], vid=inp["vid"])
+        ref = oracle.layer_forward(last, cfg.top_k, cfg.dtype, cfg.act)
+        gc.assert_close(gc.to_np64(got), ref["Y"], cfg.dtype, "Y (graph replay)")
