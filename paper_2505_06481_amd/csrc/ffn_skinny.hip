@@ -4,21 +4,23 @@
 // kernel is built around keeping many 16-byte loads of weights in flight per wavefront.
 //
 // Both products are of the form  out[r, n] = sum_k A[r, k] * W[s][n][k]  over the packed
-// (reduction-contiguous) pool.  A workgroup owns 16 output features n of one slot and all
-// rows of that slot; its four wavefronts split the reduction dimension and meet in LDS.
-// The 16 weight rows are the 16-row operand of a 16x16 matrix-core instruction and up to
-// 16 tokens are its 16 columns, so the weights pass through registers once however many
-// tokens (up to 32 per pass) the slot holds.
+// pool.  A workgroup owns a block of output features n of one slot and all rows of that
+// slot; its four wavefronts split the reduction dimension and meet in LDS.  The weight rows
+// are the row operand of a matrix-core instruction and the tokens its columns, so the
+// weights pass through registers once however many tokens (up to 32 per pass) the slot holds.
+// In the fused layer the token rows of the first product are read through the grouping
+// permutation (row perm[r] / top_k of X) instead of from a gathered copy.
 //
-// The text below describes the fp32 kernel (transposed pool, 16x16x4 matrix instructions).
-// The bf16 kernel further down follows the same plan on the fragment-packed pool with
-// 32x32x16 instructions: 32 output features per workgroup, up to 32 rows per pass.
+// fp32 kernel (skinny_kernel): transposed pool [S, N, K], 16 features per workgroup,
+// 16x16x4 matrix instructions, two 16-row token blocks per pass.  Reduction-index
+// permutation: per 256-byte step of a row, lane group g = lane/16 loads the contiguous 64
+// bytes [64g, 64g+64) as four 16-byte pieces q; piece q of every group feeds matrix
+// instruction q.  Weights and activations use the same permutation, and a sum does not care
+// in which order its terms are visited, so no shuffle is needed and every lane's global
+// loads are contiguous.
 //
-// Reduction-index permutation: per 256-byte step of a row, lane group g = lane/16 loads
-// the contiguous 64 bytes [64g, 64g+64) as four 16-byte pieces q; piece q of every group
-// feeds matrix instruction q.  Weights and activations use the same permutation, and a
-// sum does not care in which order its terms are visited, so no shuffle is needed and
-// every lane's global loads are contiguous.
+// bf16 kernel (skinny_frag_kernel): fragment-packed pool, 32 features per workgroup,
+// 32x32x16 matrix instructions, up to 32 rows per pass; see its own comment.
 #include "mmoe_internal.h"
 
 namespace mmoe {
@@ -30,13 +32,6 @@ constexpr int kSkWaves = 4;
 constexpr int kSkMB = 2;  // 16-row token blocks per pass
 
 template <typename T> struct Mma;
-template <> struct Mma<uint16_t> {  // bf16, 16x16x32: one 16-byte piece = 8 reduction elements
-    static __device__ __forceinline__ f32x4 run(u32x4 w, u32x4 x, f32x4 acc)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x),
-                                                       acc, 0, 0, 0);
-    }
-};
 template <> struct Mma<float> {  // fp32, 16x16x4: one 16-byte piece = 4 elements = 4 instructions
     static __device__ __forceinline__ f32x4 run(u32x4 w, u32x4 x, f32x4 acc)
     {

@@ -1,5 +1,7 @@
 // Step R: per-variant gate, top-k selection and coefficients (Algorithm 2, "gate(act)";
-// section 3.2).  One workgroup scores one token, its wavefronts share out the experts.
+// section 3.2).  Two launch shapes with the same arithmetic: small batches give a token to a
+// workgroup whose wavefronts share out the experts (latency); large batches give a token to
+// one wavefront that keeps the token row in registers and walks the experts (throughput).
 //
 // The logit is an fp32 sum in the fixed order the header states: lane l owns the
 // elements i with (i div 4) mod 64 == l, which is exactly what a coalesced 4-element
