@@ -190,7 +190,7 @@ def make_inputs(cfg: Config, weights: bool = True) -> Dict[str, Optional[np.ndar
     }
     if cfg.bias_alpha != 0.0:
         row = (-cfg.bias_alpha * np.log(np.arange(cfg.E) + 1.0)).astype(np.float32)
-        out["br"] = np.ascontiguousarray(np.broadcast_to(row, (cfg.V, cfg.E)))
+        out["br"] = np.tile(row, (cfg.V, 1))
     if weights:
         d, f = cfg.d_model, cfg.d_ff
         np_dt = np.float32 if dt == "f32" else np.uint16

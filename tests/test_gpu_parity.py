@@ -268,3 +268,32 @@ def test_layer_forward_in_a_captured_graph(mm, gc, oracle):
         last = dict(case.inp, X=inp["X"], vid=inp["vid"])
         ref = oracle.layer_forward(last, cfg.top_k, cfg.dtype, cfg.act)
         gc.assert_close(gc.to_np64(got), ref["Y"], cfg.dtype, "Y (graph replay)")
+
+
+def _random_configs(n, seed):
+    """Seeded sweep over shapes: both dtypes and activations, every k up to E, token counts on
+    both sides of every dispatch threshold (router variants, streaming vs tiled expert
+    kernels, one or several grouping workgroups), with and without a router bias."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        act = "relu" if i % 3 == 2 else "swiglu"
+        d = int(rng.choice([256, 512, 768, 1024]))
+        f = int(rng.choice([256, 512, 1280]))
+        V = int(rng.integers(1, 5))
+        E = int(rng.integers(1, 10))
+        k = int(rng.integers(1, min(E, 4) + 1))
+        T = int(rng.choice([1, 7, 64, 200, 511, 512, 700, 1100, 2300]))
+        if dtype == "f32":
+            T = min(T, 300)              # the fp32 oracle path is slower and fp32 never uses the tiled kernels
+        out.append(synth.Config(f"rnd{i}_{dtype}_{act}_T{T}_d{d}_f{f}_V{V}_E{E}_k{k}", T, d, f, V, E, k, dtype, act,
+                                seed=1000 + i, bias_alpha=float(rng.choice([0.0, 0.5])),
+                                vid_mode=str(rng.choice(["uniform", "zipf", "interleave"])),
+                                share_prob=float(rng.choice([0.0, 0.5, 1.0]))))
+    return out
+
+
+@pytest.mark.parametrize("cfg", _random_configs(24, seed=2024), ids=lambda c: c.name)
+def test_random_shapes(mm, gc, oracle, cfg):
+    staged_vs_oracle(mm, gc, oracle, cfg)
