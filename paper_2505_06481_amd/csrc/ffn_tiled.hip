@@ -111,6 +111,7 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
     __shared__ int base_all[kMaxS + 1];  // first row tile of each slot, partial tiles included
     __shared__ int ragged[kMaxS];      // slots with a partial last tile, most rows first
     __shared__ int n_ragged;
+    const int bm_log2 = 31 - __clz(bm);  // the tile height is a power of two: shifts, not divisions, in the serial part
     for (int s = threadIdx.x; s < S; s += 256) {
         const int o = offsets[s];
         off_s[s] = o;
@@ -124,9 +125,9 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
         for (int s = 0; s < S; ++s) {
             base[s] = run;
             base_all[s] = run_all;
-            run += cnt_s[s] / bm;
-            run_all += (cnt_s[s] + bm - 1) / bm;
-            const int rem = cnt_s[s] % bm;
+            run += cnt_s[s] >> bm_log2;
+            run_all += (cnt_s[s] + bm - 1) >> bm_log2;
+            const int rem = cnt_s[s] & (bm - 1);
             if (rem) ++bucket[(rem + 31) / 32];
         }
         base[S] = run;
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
         }
         n_ragged = at;
         for (int s = 0; s < S; ++s) {
-            const int rem = cnt_s[s] % bm;
+            const int rem = cnt_s[s] & (bm - 1);
             if (rem) ragged[bucket[(rem + 31) / 32]++] = s;
         }
         tab[L.hdr] = run + at;
@@ -153,6 +154,7 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
         // many: keep the partial tile next to the full tiles that share its weight panel
         const bool longest_first = total_m * NT < kLongestFirstBelow;
         for (int c = 0; c < 2; ++c) {
+            if (c == 1 && NT % kXcds == 0) break;  // every XCD has the same number of feature tiles: one list
             const int nt_x = c == 0 ? (NT + kXcds - 1) / kXcds : NT / kXcds;
             const int n_full = longest_first ? total_full * nt_x : 0, n = total_m * nt_x;
             for (int e = threadIdx.x; e < n; e += 256) {
@@ -185,7 +187,7 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
                 } else {
                     const int q = e - n_full;
                     const int s = ragged[q / nt_x];
-                    const int full = cnt_s[s] / bm;
+                    const int full = cnt_s[s] >> bm_log2;
                     ent = make_int4(s, q % nt_x, off_s[s] + full * bm, cnt_s[s] - full * bm);
                 }
                 lists[L.list[p][c] + e] = ent;
