@@ -69,6 +69,18 @@ def parse():
     return ap.parse_args()
 
 
+def to_dev(a):
+    """numpy array in storage form (fp32, or bf16 bit patterns as uint16) -> device tensor."""
+    import numpy as np
+    import torch
+
+    if a is None:
+        return None
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
 class HipEvents:
     """hipEvent_t handles created straight from the HIP runtime (timing enabled)."""
 
@@ -102,12 +114,9 @@ def run_workload(cfg, inp, pool, steps, warmup):
 
     from paper_2505_06481_amd import mmoe
 
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    import gpu_common as gc
-
     S = int(inp["S"])
     shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act)
-    X, Wr = gc.to_dev(inp["X"], cfg.dtype), gc.to_dev(inp["Wr"], cfg.dtype)
+    X, Wr = to_dev(inp["X"]), to_dev(inp["Wr"])
     vid, M = torch.from_numpy(inp["vid"]).cuda(), torch.from_numpy(inp["M"]).cuda()
     br = None if inp["br"] is None else torch.from_numpy(inp["br"]).cuda()
     ws = mmoe.alloc_workspace(shape)
@@ -211,14 +220,11 @@ def main():
     mmoe.lib()  # fails loudly if the HIP library is not built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    import gpu_common as gc
-
     cfg = synth.CONFIGS[a.workload]
     inp = synth.make_inputs(cfg)
     S = int(inp["S"])
     shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act)
-    W1, W3, W2 = (gc.to_dev(inp[k], cfg.dtype) for k in ("W1", "W3", "W2"))
+    W1, W3, W2 = (to_dev(inp[k]) for k in ("W1", "W3", "W2"))
     pool = mmoe.pack_weights(shape, W1, W3, W2)   # one-time repacking at pool load, untimed
     torch.cuda.synchronize()
     del W1, W3, W2
