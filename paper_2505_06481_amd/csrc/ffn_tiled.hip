@@ -389,6 +389,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
             copy_a(3, min(3, last));
 #pragma unroll
             for (int g = 0; g < kBAhead; ++g) load_bf(bq[g], g);
+            static_assert(2 * kNP + NB * kBAhead <= 63, "vmcnt is a 6-bit counter");
             asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * kNP + NB * kBAhead) : "memory");
         } else {
             // prologue: steps 0..2 into the three stages, steps 3 and 4 on their way into registers
@@ -441,6 +442,8 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
                         // rest of that slice, 8 in step t-1, 6 in this step), so vmcnt(16) leaves them
                         // landed: after the barrier every wavefront may read step t+2, whose first
                         // fragments are fetched before the next barrier.
+                        static_assert(kNP + 8 * NB >= 16, "steady state: loads issued after a copy group");
+                        static_assert(kNP + NB * kBAhead + 3 * NB >= 16, "first step: after the copies of step 2");
                         asm volatile("s_waitcnt vmcnt(16) lgkmcnt(%0)\n\ts_barrier" ::"n"(NH) : "memory");
                         copy_a(st, min(t + 4, last));  // tokens of step t+4; past the end: a harmless reload
                     } else {
