@@ -32,12 +32,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).  The figures belong
 # to one version of the kernel source; with any other version `traffic` is null.
 TRAFFIC = {
-    "ffn_tiled.hip": {"sha256": "ce2adf846015648b2712c9dc6dc80f54fa58dc8917d8cb13cc63099cb9a58258",
+    "ffn_tiled.hip": {"sha256": "ea3d13f0221bca86e72e1e5981a7f106f0b5922686061aadfb2039c84b59645e",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 13634547830, "write_bytes": 469762736},
-    "ffn_skinny.hip": {"sha256": "9105a3530f258518f599cef4194389f5c9a3547f3d2f3e1badbebe3f9da3ba4d",
+                      "fetch_bytes": 13686259162, "write_bytes": 469762528},
+    "ffn_skinny.hip": {"sha256": "e3d20992929bfea46d211c6fb4142b0d27beb9985942e3cdf8065493e4fd6502",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3067220995, "write_bytes": 3670830},
+                       "fetch_bytes": 3067185637, "write_bytes": 3670904},
 }
 
 
