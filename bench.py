@@ -63,6 +63,7 @@ def parse():
     ap.add_argument("--workload", default="mixtral_prefill_bf16_v2_t8192")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-shaped companion run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the streaming-read / matrix-loop probes")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = 96 tokens per oracle thread")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference point for HBM byte counters)")
@@ -273,6 +274,16 @@ def main():
             "stages_ms": dres["stages_ms"], "step_ms_by_events": dres["events_ms"],
             "roofline": roofline(dcfg, dres, True),
         }
+
+    if not a.no_ceilings:
+        # what this GPU delivers with nothing else in the way: a pure streaming read and a pure
+        # matrix-instruction loop (the chip clocks down under matrix load, so the second figure is
+        # well below the data-sheet peak that `roofline.peak` quotes)
+        gbs, tflops = mmoe.probe_ceilings()
+        out["achievable"] = {"stream_read_GBps": gbs, "mfma_bf16_loop_TFLOPps": tflops,
+                             "roofline_frac_of_achievable": out["roofline"]["achieved"] / tflops}
+        if "decode" in out:
+            out["decode"]["roofline_frac_of_achievable"] = out["decode"]["roofline"]["achieved"] / gbs
 
     if a.copy_calibration:
         # a plain elementwise copy of known size: reads 1 GiB, writes 1 GiB per launch

@@ -206,6 +206,16 @@ int mmoe_layer_forward_events(const mmoe_shape *shape, const void *X, const int3
 int mmoe_set_expert_tile_rows(int rows);
 
 /*
+ * Measurement aid, SYNCHRONISES the stream; not part of the layer.  Measures what this GPU
+ * delivers for the two resources that bound the expert stage: out[0] = GB/s of a pure
+ * streaming read of `buf` (DEVICE memory, `bytes` >= 64 MiB, 256-byte aligned, zero-filled by
+ * the caller; its last MiB is written), out[1] = TFLOP/s of a loop of
+ * v_mfma_f32_32x32x16_bf16 on register operands with no memory traffic.  `out` is a HOST
+ * array of two floats.  Benchmarks print these beside the data-sheet peaks.
+ */
+int mmoe_probe_ceilings(void* buf, size_t bytes, float* out, void* stream);
+
+/*
  * Debugging aid, SYNCHRONISES the stream: checks on the device that every vid[t] is in
  * [0,V) and every M[v][e] in [0,S).  Returns 0 if so, 1 if not, a negative status on
  * argument errors.  `ws` needs 256 bytes.

@@ -219,6 +219,14 @@ int mmoe_layer_forward(const mmoe_shape* shape, const void* X, const int32_t* vi
 
 int mmoe_set_expert_tile_rows(int rows) { return mmoe::set_tile_rows(rows); }
 
+int mmoe_probe_ceilings(void* buf, size_t bytes, float* out, void* stream)
+{
+    if (!buf || !out) return MMOE_ERR_NULL;
+    if (bytes < ((size_t)64 << 20)) return MMOE_ERR_WORKSPACE;
+    if (misaligned(buf, 256)) return MMOE_ERR_ALIGN;
+    return run_probe(buf, bytes, out, (hipStream_t)stream);
+}
+
 int mmoe_validate_inputs(const mmoe_shape* shape, const int32_t* vid, const int32_t* M, void* ws,
                          size_t ws_bytes, void* stream)
 {

@@ -71,6 +71,7 @@ int launch_combine(const mmoe_shape& s, const float* Yg, const int32_t* inv_perm
                    void* Y, hipStream_t st);
 int launch_pack(const mmoe_shape& s, const void* W1, const void* W3, const void* W2, void* W1p, void* W3p,
                 void* W2p, hipStream_t st);
+int run_probe(void* buf, size_t bytes, float* out, hipStream_t st);
 int launch_validate(const mmoe_shape& s, const int32_t* vid, const int32_t* M, int32_t* flag, hipStream_t st);
 
 inline int launch_status()

@@ -26,7 +26,7 @@ _TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
 EXPORTS = [
     "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
     "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_layer_forward_events",
-    "mmoe_validate_inputs", "mmoe_set_expert_tile_rows",
+    "mmoe_validate_inputs", "mmoe_set_expert_tile_rows", "mmoe_probe_ceilings",
 ]
 
 
@@ -73,6 +73,8 @@ def lib():
         L.mmoe_layer_forward.argtypes = [sp] + [vp] * 10 + [sz, vp]
         L.mmoe_layer_forward_events.argtypes = [sp] + [vp] * 10 + [sz, vp, vp]
         L.mmoe_validate_inputs.argtypes = [sp, vp, vp, vp, sz, vp]
+        L.mmoe_set_expert_tile_rows.argtypes = [i]
+        L.mmoe_probe_ceilings.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_float), vp]
         for n in EXPORTS[2:]:
             getattr(L, n).restype = i
         _lib = L
@@ -215,3 +217,12 @@ def validate_inputs(shape: Shape, vid, M, ws) -> bool:
 def set_expert_tile_rows(rows: int) -> None:
     """Tuning knob of the matrix-core expert kernels: 0 = by shape, 128 or 256 = forced."""
     _check(lib().mmoe_set_expert_tile_rows(int(rows)), "mmoe_set_expert_tile_rows")
+
+
+def probe_ceilings(gib: int = 4):
+    """(GB/s of a pure streaming read, TFLOP/s of a pure bf16 matrix-instruction loop) on this GPU."""
+    buf = torch.zeros(gib << 30, dtype=torch.uint8, device="cuda")
+    out = (ctypes.c_float * 2)()
+    _check(lib().mmoe_probe_ceilings(_ptr(buf, torch.uint8, None, "buf"), buf.numel(), out, _stream()),
+           "mmoe_probe_ceilings")
+    return float(out[0]), float(out[1])

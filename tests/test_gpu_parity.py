@@ -297,3 +297,9 @@ def _random_configs(n, seed):
 @pytest.mark.parametrize("cfg", _random_configs(24, seed=2024), ids=lambda c: c.name)
 def test_random_shapes(mm, gc, oracle, cfg):
     staged_vs_oracle(mm, gc, oracle, cfg)
+
+
+def test_ceiling_probe_reports_plausible_rates(mm):
+    gbs, tflops = mm.probe_ceilings(gib=1)
+    assert 2000.0 < gbs < 8000.0, gbs          # below the 8 TB/s data-sheet peak, above a third of it
+    assert 500.0 < tflops < 2500.0, tflops     # below the 2.5 PFLOP/s data-sheet peak

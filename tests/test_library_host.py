@@ -90,3 +90,13 @@ def test_tile_rows_knob_accepts_only_its_three_values(mm):
     for bad in (64, 512, -1, 100):
         assert L.mmoe_set_expert_tile_rows(bad) == -2
     assert L.mmoe_set_expert_tile_rows(0) == 0
+
+
+def test_probe_rejects_bad_arguments_before_touching_the_gpu(mm):
+    L = mm.lib()
+    out = (ctypes.c_float * 2)()
+    p = ctypes.c_void_p(4096)
+    assert L.mmoe_probe_ceilings(None, ctypes.c_size_t(1 << 30), out, None) == -1
+    assert L.mmoe_probe_ceilings(p, ctypes.c_size_t(1 << 30), None, None) == -1
+    assert L.mmoe_probe_ceilings(p, ctypes.c_size_t(1 << 20), out, None) == -6     # buffer too small
+    assert L.mmoe_probe_ceilings(ctypes.c_void_p(4097), ctypes.c_size_t(1 << 30), out, None) == -7
