@@ -52,7 +52,6 @@ constexpr int kLongestFirstBelow = 8 * 256;  // tiles of a product: below this, 
 #endif
 constexpr int kNtGroup = MMOE_TILED_NTGROUP;  // feature tiles whose workgroups start back to back on the same token panel
 
-typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 // silu(g) * u with the hardware exponential and reciprocal (about 1 ulp each; the result is
@@ -64,7 +63,7 @@ __device__ __forceinline__ float silu_mul_t(float g, float u)
 }
 
 // Tile lists written by tile_table_kernel, one workgroup, from the device-side `offsets`:
-//   tab[0]                      number of row tiles, sum_s ceil(count_s / 256)
+//   tab[0]                      number of row tiles, sum_s ceil(count_s / tile height)
 //   four lists of int4 entries  {slot, feature tile within the XCD, first row, rows valid},
 //   one per (product, feature tiles per XCD): a product with NT feature tiles gives XCD x
 //   the tiles nt with nt mod 8 == x, that is ceil or floor of NT/8 of them; list entry
@@ -74,7 +73,7 @@ __device__ __forceinline__ float silu_mul_t(float g, float u)
 //   apart, so the ones that share a token panel and the ones that share a weight panel both
 //   run close enough in time to find the panel in L2.  A product with
 //   few tiles per compute unit (fewer than kLongestFirstBelow tiles in all) lists the longest
-//   work first: every full 256-row tile in that order, and after them the partial last tiles
+//   work first: every full tile in that order, and after them the partial last tiles
 //   of the slots, those with the most rows first, so that the short ones fill the end of the
 //   launch.
 struct TileLists {
