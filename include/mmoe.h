@@ -39,7 +39,7 @@
  * Limits
  *   d_model and d_ff multiples of 256; E <= 256; top_k <= min(E, 8); S <= 1024;
  *   P*max(d,f) < 2^35, and < 2^31 for bf16 batches large enough for the matrix-core expert
- *   kernels (P > 48*S): otherwise MMOE_ERR_LIMIT.  SWIGLU needs W3, RELU needs W3 == NULL.
+ *   kernels (P > 16*S): otherwise MMOE_ERR_LIMIT.  SWIGLU needs W3, RELU needs W3 == NULL.
  */
 #ifndef MMOE_H
 #define MMOE_H

@@ -546,10 +546,11 @@ static void tiled_nts(const mmoe_shape& s, int& nt_up, int& nt_down)
     nt_down = s.d_model / kBN;
 }
 
-// Tile height: 256 rows when the batch fills the chip several times over; 128 rows (two
-// workgroups per compute unit, more and shorter tiles) when the down product, which has the
-// fewest tiles, would otherwise leave compute units idle.  The host knows P and S, not the
-// counts: a slot is taken to end in half a tile.
+// Tile height: 256 rows when the batch fills the chip; 128 rows (two workgroups per compute
+// unit, more and shorter tiles) when the down product, which has the fewest tiles, would
+// otherwise leave a third or more of the compute units idle.  The host knows P and S, not the
+// counts: a slot is taken to end in half a tile.  (Measured on the Mixtral shape: 128 rows win
+// up to 384 tokens, 256 rows from 512 tokens on.)
 static int g_tile_rows = 0;  // 0: by shape; 128 or 256: forced (mmoe_set_expert_tile_rows)
 
 int set_tile_rows(int rows)
@@ -564,7 +565,7 @@ static int tile_rows(const mmoe_shape& s, int nt_down)
     if (g_tile_rows) return g_tile_rows;
     const int64_t P = (int64_t)s.T * s.top_k;
     const int64_t tiles = (P / kBMBig + (s.S + 1) / 2) * nt_down;
-    return tiles < 2 * 256 ? kBMSmall : kBMBig;
+    return tiles < 170 ? kBMSmall : kBMBig;
 }
 
 size_t tiled_table_bytes(const mmoe_shape& s)

@@ -74,6 +74,8 @@ SMALL = [
     synth.Config("s_f32_relu", 33, 256, 512, 2, 4, 1, "f32", "relu", seed=3),
     synth.Config("s_f32_swiglu", 50, 512, 256, 2, 4, 2, "f32", "swiglu", seed=4, bias_alpha=0.5),
     synth.Config("s_f32_many_rows", 300, 256, 256, 1, 2, 1, "f32", "relu", seed=5),     # > 32 rows: passes
+    # few rows per slot on average, but a biased router fills one slot beyond a 32-row pass
+    synth.Config("s_bf16_skewed_passes", 100, 512, 256, 1, 8, 1, "bf16", "swiglu", seed=26, bias_alpha=3.0),
     # matrix-core tiled kernels (many rows per slot), ragged tails, several tiles per slot
     synth.Config("t_bf16_swiglu", 700, 512, 768, 2, 4, 2, "bf16", "swiglu", seed=6),
     synth.Config("t_bf16_relu", 900, 256, 512, 3, 4, 1, "bf16", "relu", seed=7),
