@@ -231,7 +231,8 @@ def main():
     del W1, W3, W2
     torch.cuda.empty_cache()
 
-    skinny = cfg.dtype == "f32" or cfg.T * cfg.top_k <= 16 * S   # the library's dispatch rule
+    small_experts = cfg.d_model * cfg.d_ff <= (4 << 20)
+    skinny = cfg.dtype == "f32" or cfg.T * cfg.top_k <= (32 if small_experts else 16) * S   # the library's dispatch rule
     res = run_workload(cfg, inp, pool, a.steps, a.warmup)
     ms = res["ms_per_step"]
     nw = 3 if cfg.act == "swiglu" else 2

@@ -39,7 +39,7 @@
  * Limits
  *   d_model and d_ff multiples of 256; E <= 256; top_k <= min(E, 8); S <= 1024;
  *   P*max(d,f) < 2^35, and < 2^31 for bf16 batches large enough for the matrix-core expert
- *   kernels (P > 16*S): otherwise MMOE_ERR_LIMIT.  SWIGLU needs W3, RELU needs W3 == NULL.
+ *   kernels (P > 16*S, or 32*S when d*f <= 4 Mi): otherwise MMOE_ERR_LIMIT.  SWIGLU needs W3, RELU needs W3 == NULL.
  */
 #ifndef MMOE_H
 #define MMOE_H
@@ -197,8 +197,9 @@ int mmoe_layer_forward_events(const mmoe_shape *shape, const void *X, const int3
 /*
  * Tuning knob, host only, process-wide (not thread-safe against concurrent calls of the
  * expert stage): the number of token rows per tile of the matrix-core expert kernels.
- * 0 (the default) chooses by shape: 256 rows when the batch fills the chip several times
- * over, 128 rows (more, shorter tiles; two workgroups per compute unit) otherwise.  128
+ * 0 (the default) chooses by shape: 128 rows (two workgroups per compute unit) when tiles
+ * are short-lived (d_model <= 1024, or fewer than 64 rows per slot on average), 256 rows
+ * otherwise.  128
  * or 256 forces that height for every later call.  Either height sums every output
  * element in the same order, so the results are bit-identical.  Returns 0, or MMOE_ERR_DIM
  * for any other value.

@@ -546,11 +546,13 @@ static void tiled_nts(const mmoe_shape& s, int& nt_up, int& nt_down)
     nt_down = s.d_model / kBN;
 }
 
-// Tile height: 256 rows when the batch fills the chip; 128 rows (two workgroups per compute
-// unit, more and shorter tiles) when the down product, which has the fewest tiles, would
-// otherwise leave a third or more of the compute units idle.  The host knows P and S, not the
-// counts: a slot is taken to end in half a tile.  (Measured on the Mixtral shape: 128 rows win
-// up to 384 tokens, 256 rows from 512 tokens on.)
+// Tile height: 128 rows (two workgroups per compute unit, so one's prologue and epilogue hide
+// behind the other's main loop) when a tile is short-lived -- a short reduction in the up
+// product, or slots with few rows -- and 256 rows (deeper weight prefetch, half the weight
+// traffic per row) otherwise.  The host knows P and S, not the counts.  Measured with each
+// height forced: on the Switch shape (d = 768) 128 rows win at every batch size up to 16384
+// tokens; on the Mixtral shape (d = 4096) they win up to 59 rows per slot (384 tokens) and
+// lose from 79 rows per slot (512 tokens) on.
 static int g_tile_rows = 0;  // 0: by shape; 128 or 256: forced (mmoe_set_expert_tile_rows)
 
 int set_tile_rows(int rows)
@@ -560,12 +562,11 @@ int set_tile_rows(int rows)
     return MMOE_OK;
 }
 
-static int tile_rows(const mmoe_shape& s, int nt_down)
+static int tile_rows(const mmoe_shape& s)
 {
     if (g_tile_rows) return g_tile_rows;
     const int64_t P = (int64_t)s.T * s.top_k;
-    const int64_t tiles = (P / kBMBig + (s.S + 1) / 2) * nt_down;
-    return tiles < 170 ? kBMSmall : kBMBig;
+    return (s.d_model <= 1024 || P < (int64_t)64 * s.S) ? kBMSmall : kBMBig;
 }
 
 size_t tiled_table_bytes(const mmoe_shape& s)
@@ -607,7 +608,7 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
     if ((int64_t)P * (d > f ? d : f) >= ((int64_t)1 << 31)) return MMOE_ERR_LIMIT;  // 32-bit byte offsets inside a panel
     int nt_up, nt_down;
     tiled_nts(s, nt_up, nt_down);
-    const int bm = tile_rows(s, nt_down);
+    const int bm = tile_rows(s);
     const TileLists L = tile_lists(P, s.S, nt_up, nt_down, bm);
     hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, bm, L);
     bool event_failed = false;

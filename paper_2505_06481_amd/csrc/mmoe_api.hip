@@ -48,11 +48,14 @@ bool use_skinny(const mmoe_shape& s)
     // fp32 always streams (fp32 MFMA, full precision).  bf16 streams when a slot sees few
     // rows: the weights are then read once from HBM and that read is the bound.  The
     // streaming kernel takes 32 rows of a slot per pass over its weights, so it only pays
-    // while the fullest slot stays near that; measured on the Mixtral shape it wins up to an
-    // average of 16 rows per slot and loses quickly beyond (1.21 ms against 0.83 ms at 40).
+    // while the fullest slot stays near that.  Measured with each kernel forced: on the
+    // Mixtral shape (352 MB a slot) it wins up to an average of 16 rows per slot and loses
+    // quickly beyond (1.21 ms against 0.83 ms at 40); on the Switch shape (9 MB a slot, a
+    // second pass finds the weights in cache) up to 32.
     if (s.dtype == MMOE_F32) return true;
-    int64_t P = (int64_t)s.T * s.top_k;
-    return P <= (int64_t)16 * s.S;
+    const int64_t P = (int64_t)s.T * s.top_k;
+    const bool small_experts = (int64_t)s.d_model * s.d_ff <= ((int64_t)4 << 20);
+    return P <= (int64_t)(small_experts ? 32 : 16) * s.S;
 }
 
 static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
