@@ -32,12 +32,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).  The figures belong
 # to one version of the kernel source; with any other version `traffic` is null.
 TRAFFIC = {
-    "ffn_tiled.hip": {"sha256": "51a0a3b141c20115825b19350c10a1f1851bdcfb70eb4dae5bf0797d891aa406",
+    "ffn_tiled.hip": {"sha256": "88d6b37054785cacd2883fe8b65341c9c08dfe72aa3cb171bc16c1df317ab79c",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 13721444375, "write_bytes": 469762688},
+                      "fetch_bytes": 13562752784, "write_bytes": 469762288},
     "ffn_skinny.hip": {"sha256": "e3d20992929bfea46d211c6fb4142b0d27beb9985942e3cdf8065493e4fd6502",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3067176027, "write_bytes": 3670784},
+                       "fetch_bytes": 3067327010, "write_bytes": 3670863},
 }
 
 
