@@ -64,6 +64,10 @@ def parse():
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-shaped companion run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the streaming-read / matrix-loop probes")
+    ap.add_argument("--zero-pool", action="store_true",
+                    help="diagnostic: same batch, routing and launch configuration, but an all-zero expert pool "
+                         "(nothing toggles in the multipliers): separates the chip's power limit from the "
+                         "kernels' cycle efficiency; the result is not a benchmark figure")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = 96 tokens per oracle thread")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference point for HBM byte counters)")
@@ -227,6 +231,10 @@ def main():
     shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act)
     W1, W3, W2 = (to_dev(inp[k]) for k in ("W1", "W3", "W2"))
     pool = mmoe.pack_weights(shape, W1, W3, W2)   # one-time repacking at pool load, untimed
+    if a.zero_pool:
+        for w in pool:
+            if w is not None:
+                w.zero_()
     torch.cuda.synchronize()
     del W1, W3, W2
     torch.cuda.empty_cache()
@@ -249,7 +257,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": cfg.dtype,
-        "data": "synthetic",
+        "data": "synthetic" if not a.zero_pool else "synthetic tokens and routers, ALL-ZERO expert pool (diagnostic)",
         "config": {"workload": cfg.name, "T": cfg.T, "d_model": cfg.d_model, "d_ff": cfg.d_ff, "V": cfg.V,
                    "E": cfg.E, "top_k": cfg.top_k, "S": S, "act": cfg.act, "seed": cfg.seed,
                    "slot_rows_min_med_max": [int(res["counts"].min()), int(sorted(res["counts"])[S // 2]),
