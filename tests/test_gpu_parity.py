@@ -176,13 +176,14 @@ def test_benchmark_shapes_full_parity(mm, gc, oracle, name):
     staged_vs_oracle(mm, gc, oracle, synth.CONFIGS[name])
 
 
-@pytest.mark.parametrize("name", ["mixtral_prefill_bf16_v2_t8192", "mixtral_skew_bf16_v4_t16384"])
-def test_benchmark_shapes_sampled_parity(mm, gc, oracle, name):
+@pytest.mark.parametrize("name,seed", [("mixtral_prefill_bf16_v2_t8192", 0), ("mixtral_skew_bf16_v4_t16384", 0),
+                                       ("mixtral_prefill_bf16_v2_t8192", 1)])
+def test_benchmark_shapes_sampled_parity(mm, gc, oracle, name, seed):
     """Full-size layers in the benchmark's launch configuration: integer outputs on every
     token, outputs on a seeded sample of rows (including rows of the smallest and the
     largest slot) that the oracle evaluates one by one."""
-    cfg = synth.CONFIGS[name]
-    print(f"case {name}: generating", flush=True)
+    cfg = synth.CONFIGS[name].replace(seed=seed)
+    print(f"case {name} seed {seed}: generating", flush=True)
     case = gc.DeviceCase(cfg)
     inp, sh = case.inp, case.shape
     print("routing oracle", flush=True)
