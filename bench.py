@@ -34,10 +34,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 TRAFFIC = {
     "ffn_tiled.hip": {"sha256": "88d6b37054785cacd2883fe8b65341c9c08dfe72aa3cb171bc16c1df317ab79c",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 13562752784, "write_bytes": 469762288},
+                      "fetch_bytes": 13594797757, "write_bytes": 469762592},
     "ffn_skinny.hip": {"sha256": "e3d20992929bfea46d211c6fb4142b0d27beb9985942e3cdf8065493e4fd6502",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3067327010, "write_bytes": 3670863},
+                       "fetch_bytes": 3067235291, "write_bytes": 3670740},
 }
 
 
