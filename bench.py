@@ -32,12 +32,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).  The figures belong
 # to one version of the kernel source; with any other version `traffic` is null.
 TRAFFIC = {
-    "ffn_tiled.hip": {"sha256": "88d6b37054785cacd2883fe8b65341c9c08dfe72aa3cb171bc16c1df317ab79c",
+    "ffn_tiled.hip": {"sha256": "02be35afa1ba2a7c3576abcb2fc02adada79f7bb52efe8ff9face40709e17304",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 13594797757, "write_bytes": 469762592},
+                      "fetch_bytes": 13700513403, "write_bytes": 469762288},
     "ffn_skinny.hip": {"sha256": "e3d20992929bfea46d211c6fb4142b0d27beb9985942e3cdf8065493e4fd6502",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3067235291, "write_bytes": 3670740},
+                       "fetch_bytes": 3067231979, "write_bytes": 3670654},
 }
 
 
@@ -239,8 +239,7 @@ def main():
     del W1, W3, W2
     torch.cuda.empty_cache()
 
-    small_experts = cfg.d_model * cfg.d_ff <= (4 << 20)
-    skinny = cfg.dtype == "f32" or cfg.T * cfg.top_k <= (32 if small_experts else 16) * S   # the library's dispatch rule
+    skinny, tile_rows = mmoe.expert_plan(shape)   # which expert-stage kernels the library uses for this shape
     res = run_workload(cfg, inp, pool, a.steps, a.warmup)
     ms = res["ms_per_step"]
     nw = 3 if cfg.act == "swiglu" else 2
@@ -262,7 +261,8 @@ def main():
                    "E": cfg.E, "top_k": cfg.top_k, "S": S, "act": cfg.act, "seed": cfg.seed,
                    "slot_rows_min_med_max": [int(res["counts"].min()), int(sorted(res["counts"])[S // 2]),
                                              int(res["counts"].max())],
-                   "slot_rows": [int(c) for c in res["counts"]]},
+                   "slot_rows": [int(c) for c in res["counts"]],
+                   "expert_kernels": "weight-streaming" if skinny else f"matrix-core, {tile_rows}-row tiles"},
         "layer_tflops": layer_flops / (ms * 1e-3) / 1e12,
         "stages_ms": res["stages_ms"],
         "step_ms_by_events": res["events_ms"],

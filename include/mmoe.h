@@ -207,6 +207,15 @@ int mmoe_layer_forward_events(const mmoe_shape *shape, const void *X, const int3
 int mmoe_set_expert_tile_rows(int rows);
 
 /*
+ * Host only, pure (apart from reading the knob above): which expert-stage kernels
+ * mmoe_expert_ffn and mmoe_layer_forward will use for this shape.  *streaming = 1: the
+ * weight-streaming kernels (every fp32 shape; bf16 with few rows per slot), *tile_rows = 32
+ * (rows of a slot per pass over its weights); *streaming = 0: the matrix-core kernels with
+ * tiles of *tile_rows (128 or 256) token rows.  The choice depends on the shape only.
+ */
+int mmoe_expert_plan(const mmoe_shape *shape, int *streaming, int *tile_rows);
+
+/*
  * Measurement aid, SYNCHRONISES the stream; not part of the layer.  Measures what this GPU
  * delivers for the two resources that bound the expert stage: out[0] = GB/s of a pure
  * streaming read of `buf` (DEVICE memory, `bytes` >= 64 MiB, 256-byte aligned, zero-filled by

@@ -562,7 +562,7 @@ int set_tile_rows(int rows)
     return MMOE_OK;
 }
 
-static int tile_rows(const mmoe_shape& s)
+int planned_tile_rows(const mmoe_shape& s)
 {
     if (g_tile_rows) return g_tile_rows;
     const int64_t P = (int64_t)s.T * s.top_k;
@@ -608,7 +608,7 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
     if ((int64_t)P * (d > f ? d : f) >= ((int64_t)1 << 31)) return MMOE_ERR_LIMIT;  // 32-bit byte offsets inside a panel
     int nt_up, nt_down;
     tiled_nts(s, nt_up, nt_down);
-    const int bm = tile_rows(s);
+    const int bm = planned_tile_rows(s);
     const TileLists L = tile_lists(P, s.S, nt_up, nt_down, bm);
     hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, bm, L);
     bool event_failed = false;

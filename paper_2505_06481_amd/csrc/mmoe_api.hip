@@ -225,6 +225,16 @@ int mmoe_layer_forward(const mmoe_shape* shape, const void* X, const int32_t* vi
 
 int mmoe_set_expert_tile_rows(int rows) { return mmoe::set_tile_rows(rows); }
 
+int mmoe_expert_plan(const mmoe_shape* shape, int* streaming, int* tile_rows)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!streaming || !tile_rows) return MMOE_ERR_NULL;
+    *streaming = use_skinny(*shape) ? 1 : 0;
+    *tile_rows = *streaming ? 32 : planned_tile_rows(*shape);
+    return MMOE_OK;
+}
+
 int mmoe_probe_ceilings(void* buf, size_t bytes, float* out, void* stream)
 {
     if (!buf || !out) return MMOE_ERR_NULL;

@@ -67,6 +67,7 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
                      hipStream_t st, hipEvent_t mid = nullptr);
 size_t tiled_table_bytes(const mmoe_shape& s);
 int set_tile_rows(int rows);
+int planned_tile_rows(const mmoe_shape& s);  // tile height launch_ffn_tiled would use for this shape
 int launch_combine(const mmoe_shape& s, const float* Yg, const int32_t* inv_perm, const float* topk_w,
                    void* Y, hipStream_t st);
 int launch_pack(const mmoe_shape& s, const void* W1, const void* W3, const void* W2, void* W1p, void* W3p,

@@ -26,7 +26,7 @@ _TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
 EXPORTS = [
     "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
     "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_layer_forward_events",
-    "mmoe_validate_inputs", "mmoe_set_expert_tile_rows", "mmoe_probe_ceilings",
+    "mmoe_validate_inputs", "mmoe_set_expert_tile_rows", "mmoe_probe_ceilings", "mmoe_expert_plan",
 ]
 
 
@@ -74,6 +74,7 @@ def lib():
         L.mmoe_layer_forward_events.argtypes = [sp] + [vp] * 10 + [sz, vp, vp]
         L.mmoe_validate_inputs.argtypes = [sp, vp, vp, vp, sz, vp]
         L.mmoe_set_expert_tile_rows.argtypes = [i]
+        L.mmoe_expert_plan.argtypes = [sp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.mmoe_probe_ceilings.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_float), vp]
         for n in EXPORTS[2:]:
             getattr(L, n).restype = i
@@ -226,3 +227,11 @@ def probe_ceilings(gib: int = 4):
     _check(lib().mmoe_probe_ceilings(_ptr(buf, torch.uint8, None, "buf"), buf.numel(), out, _stream()),
            "mmoe_probe_ceilings")
     return float(out[0]), float(out[1])
+
+
+def expert_plan(shape: Shape):
+    """(streaming, tile_rows): the expert-stage kernels the library will use for this shape."""
+    streaming, rows = ctypes.c_int(), ctypes.c_int()
+    _check(lib().mmoe_expert_plan(ctypes.byref(shape), ctypes.byref(streaming), ctypes.byref(rows)),
+           "mmoe_expert_plan")
+    return bool(streaming.value), int(rows.value)

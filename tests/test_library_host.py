@@ -100,3 +100,28 @@ def test_probe_rejects_bad_arguments_before_touching_the_gpu(mm):
     assert L.mmoe_probe_ceilings(p, ctypes.c_size_t(1 << 30), None, None) == -1
     assert L.mmoe_probe_ceilings(p, ctypes.c_size_t(1 << 20), out, None) == -6     # buffer too small
     assert L.mmoe_probe_ceilings(ctypes.c_void_p(4097), ctypes.c_size_t(1 << 30), out, None) == -7
+
+
+def test_expert_plan_follows_the_documented_dispatch(mm):
+    from paper_2505_06481_amd import synth
+
+    def plan(name_or_cfg, S):
+        c = synth.CONFIGS[name_or_cfg] if isinstance(name_or_cfg, str) else name_or_cfg
+        return mm.expert_plan(mm.make_shape(c.T, c.d_model, c.d_ff, c.V, c.E, S, c.top_k, c.dtype, c.act))
+
+    assert plan("switch8_fp32_v2_t128", 12) == (True, 32)            # fp32 always streams
+    assert plan("mixtral_decode_bf16_v2_t64", 13) == (True, 32)      # 10 rows per slot
+    assert plan("switch8_bf16_v4_t4096", 20) == (False, 128)         # short reduction: 128-row tiles
+    assert plan("mixtral_prefill_bf16_v2_t8192", 13) == (False, 256)
+    assert plan("mixtral_skew_bf16_v4_t16384", 20) == (False, 256)
+    mix = synth.CONFIGS["mixtral_decode_bf16_v2_t64"]
+    assert plan(mix.replace(T=104), 13) == (True, 32)                # 16 rows per slot: still streaming
+    assert plan(mix.replace(T=105), 13) == (False, 128)              # beyond: matrix-core kernels, small tiles
+    assert plan(mix.replace(T=415), 13) == (False, 128)              # under 64 rows per slot
+    assert plan(mix.replace(T=416), 13) == (False, 256)
+    mm.set_expert_tile_rows(128)
+    try:
+        assert plan("mixtral_prefill_bf16_v2_t8192", 13) == (False, 128)   # the knob overrides the height only
+        assert plan("mixtral_decode_bf16_v2_t64", 13) == (True, 32)
+    finally:
+        mm.set_expert_tile_rows(0)
