@@ -65,7 +65,8 @@ typedef enum {
     MMOE_ERR_ALIGN = -7,     /* a tensor pointer is not 16-byte (ws: 256-byte) aligned   */
     MMOE_ERR_MULTIPLE = -8,  /* d_model or d_ff is not a multiple of 256                 */
     MMOE_ERR_LIMIT = -9,     /* E, S or the problem size exceeds the limits above        */
-    MMOE_ERR_LAUNCH = -10    /* the HIP runtime refused a kernel launch                  */
+    MMOE_ERR_LAUNCH = -10,   /* the HIP runtime refused a kernel launch                  */
+    MMOE_ERR_STATIC_LIMIT = -11 /* the shape needs more than MMOE_STATIC_WORKSPACE_BYTES     */
 } mmoe_status;
 
 typedef struct {
@@ -170,6 +171,27 @@ int mmoe_combine(const mmoe_shape *shape, const float *Yg, const int32_t *inv_pe
 int mmoe_layer_forward(const mmoe_shape *shape, const void *X, const int32_t *vid, const void *Wr,
                        const float *br, const int32_t *M, const void *W1p, const void *W3p,
                        const void *W2p, void *Y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * mmoe_layer_forward for callers that cannot allocate device memory or hand over a workspace:
+ * code that runs under HIP graph capture, tight serving loops (one decode step after the
+ * other), harnesses that forbid allocation.  Same arguments without `ws`; same kernels, same
+ * results bit for bit.  The intermediates live in a fixed array of
+ * MMOE_STATIC_WORKSPACE_BYTES in device memory that belongs to the library's code object (each
+ * GPU the library runs on holds its own copy until the process ends).  The call allocates and
+ * frees nothing.  A shape with mmoe_workspace_bytes() above that size is refused with
+ * MMOE_ERR_STATIC_LIMIT before anything is launched (64 MiB covers decode-shaped batches: up to
+ * about 700 tokens of the Mixtral shape, 6000 of the Switch shape).
+ * Every call on one GPU uses that GPU's one array, whatever the stream: two calls that overlap
+ * in time on one GPU race; order them (same stream, or events).  Nothing in the array has to
+ * start at zero: every intermediate is written before it is read, so the contents left by an
+ * earlier call do not matter.  The array's address is looked up on the first call on each
+ * device; make that call outside of any stream capture.
+ */
+#define MMOE_STATIC_WORKSPACE_BYTES (64u << 20)
+int mmoe_layer_forward_static(const mmoe_shape *shape, const void *X, const int32_t *vid,
+                              const void *Wr, const float *br, const int32_t *M, const void *W1p,
+                              const void *W3p, const void *W2p, void *Y, void *stream);
 
 /*
  * mmoe_layer_forward with timing marks, for benchmarks and profilers.  `events` is a HOST

@@ -1,5 +1,7 @@
 // C-ABI entry points of libmmoe: argument checks, workspace carving, stage sequencing.
 // Every step of the layer runs in the HIP kernels of the other translation units.
+#include <mutex>
+
 #include "mmoe_internal.h"
 
 namespace mmoe {
@@ -86,6 +88,9 @@ const char* mmoe_strerror(int status)
         case MMOE_ERR_MULTIPLE: return "d_model and d_ff must be multiples of 256";
         case MMOE_ERR_LIMIT: return "E, S or the problem size exceeds the library's limits";
         case MMOE_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+        case MMOE_ERR_STATIC_LIMIT:
+            return "the shape needs more scratch than mmoe_layer_forward_static holds "
+                   "(MMOE_STATIC_WORKSPACE_BYTES); use mmoe_layer_forward with a workspace";
         default: return "unknown status";
     }
 }
@@ -221,6 +226,46 @@ int mmoe_layer_forward(const mmoe_shape* shape, const void* X, const int32_t* vi
                        void* Y, void* ws, size_t ws_bytes, void* stream)
 {
     return mmoe_layer_forward_events(shape, X, vid, Wr, br, M, W1p, W3p, W2p, Y, ws, ws_bytes, stream, nullptr);
+}
+
+// ---- the layer for callers that cannot allocate --------------------------------------------
+// Same kernels as mmoe_layer_forward; the intermediates live in a fixed array in device memory
+// that is part of the loaded code object instead of in a caller's workspace.  Each GPU holds its
+// own copy of the array at its own address; the address is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[MMOE_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, null until looked up
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MMOE_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MMOE_ERR_LAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MMOE_OK;
+}
+}  // namespace
+
+int mmoe_layer_forward_static(const mmoe_shape* shape, const void* X, const int32_t* vid, const void* Wr,
+                              const float* br, const int32_t* M, const void* W1p, const void* W3p,
+                              const void* W2p, void* Y, void* stream)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (ws_layout(*shape).total > (size_t)MMOE_STATIC_WORKSPACE_BYTES) return MMOE_ERR_STATIC_LIMIT;
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws))) return rc;
+    return mmoe_layer_forward_events(shape, X, vid, Wr, br, M, W1p, W3p, W2p, Y, ws,
+                                     (size_t)MMOE_STATIC_WORKSPACE_BYTES, stream, nullptr);
 }
 
 int mmoe_set_expert_tile_rows(int rows) { return mmoe::set_tile_rows(rows); }

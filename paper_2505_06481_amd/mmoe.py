@@ -26,7 +26,7 @@ _TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
 EXPORTS = [
     "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
     "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_layer_forward_events",
-    "mmoe_validate_inputs", "mmoe_set_expert_tile_rows", "mmoe_probe_ceilings", "mmoe_expert_plan",
+    "mmoe_layer_forward_static", "mmoe_validate_inputs", "mmoe_set_expert_tile_rows", "mmoe_probe_ceilings", "mmoe_expert_plan",
 ]
 
 
@@ -72,6 +72,7 @@ def lib():
         L.mmoe_combine.argtypes = [sp] + [vp] * 5
         L.mmoe_layer_forward.argtypes = [sp] + [vp] * 10 + [sz, vp]
         L.mmoe_layer_forward_events.argtypes = [sp] + [vp] * 10 + [sz, vp, vp]
+        L.mmoe_layer_forward_static.argtypes = [sp] + [vp] * 10
         L.mmoe_validate_inputs.argtypes = [sp, vp, vp, vp, sz, vp]
         L.mmoe_set_expert_tile_rows.argtypes = [i]
         L.mmoe_expert_plan.argtypes = [sp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
@@ -203,6 +204,26 @@ def layer_forward(shape: Shape, X, vid, Wr, br, M, W1p, W3p, W2p, ws, Y=None, ev
                                   _ptr(Y, dt, shape.T * d, "Y"), _ptr(ws, torch.uint8, None, "ws"), ws.numel(),
                                   _stream(), events)
     _check(rc, "mmoe_layer_forward")
+    return Y
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def layer_forward_static(shape: Shape, X, vid, Wr, br, M, W1p, W3p, W2p, Y=None):
+    """The layer without a workspace argument (intermediates in the library's fixed device array)."""
+    dt = _TORCH_DT[shape.dtype]
+    S, d, f = shape.S, shape.d_model, shape.d_ff
+    if Y is None:
+        Y = torch.empty((shape.T, d), dtype=dt, device=X.device)
+    rc = lib().mmoe_layer_forward_static(ctypes.byref(shape), _ptr(X, dt, shape.T * d, "X"),
+                                         _ptr(vid, torch.int32, shape.T, "vid"),
+                                         _ptr(Wr, dt, shape.V * shape.E * d, "Wr"),
+                                         _ptr(br, torch.float32, shape.V * shape.E, "br"),
+                                         _ptr(M, torch.int32, shape.V * shape.E, "M"),
+                                         _ptr(W1p, dt, S * d * f, "W1p"), _ptr(W3p, dt, S * d * f, "W3p"),
+                                         _ptr(W2p, dt, S * d * f, "W2p"), _ptr(Y, dt, shape.T * d, "Y"), _stream())
+    _check(rc, "mmoe_layer_forward_static")
     return Y
 
 

@@ -71,7 +71,13 @@ def test_bad_arguments_become_error_codes(mm):
     assert L.mmoe_pack_weights(ctypes.byref(gated), p, none, p, p, p, p, none) == -5
     assert L.mmoe_combine(ctypes.byref(ok), none, p, p, p, none) == -1
     assert L.mmoe_remap_permute(ctypes.byref(ok), p, p, p, p, p, p, p, p, p, p, none, 0, none) == -6
-    for code in range(0, -11, -1):
+    # the entry point without a workspace refuses, before any GPU call, what its fixed array cannot hold
+    big = mm.make_shape(8192, 4096, 14336, 2, 8, 12, 2, "bf16", "swiglu")
+    assert mm.workspace_bytes(big) > mm.STATIC_WORKSPACE_BYTES
+    assert L.mmoe_layer_forward_static(ctypes.byref(big), p, p, p, none, p, p, p, p, p, none) == -11
+    assert L.mmoe_layer_forward_static(ctypes.byref(mm.make_shape(0, 256, 256, 1, 2, 2, 1, "f32", "relu")),
+                                       p, p, p, none, p, p, none, p, p, none) == -2
+    for code in range(0, -12, -1):
         assert mm.strerror(code) != "unknown status"
     assert mm.strerror(-99) == "unknown status"
 
