@@ -62,7 +62,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="mixtral_prefill_bf16_v2_t8192")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-shaped companion run")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing and the parity block")
+    ap.add_argument("--no-second-seed", action="store_true", help="skip the robustness row (same workload, seed + 1)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the streaming-read / matrix-loop probes")
     ap.add_argument("--zero-pool", action="store_true",
                     help="diagnostic: same batch, routing and launch configuration, but an all-zero expert pool "
@@ -156,11 +157,25 @@ def run_workload(cfg, inp, pool, steps, warmup):
     per_step = stage_ms.sum(axis=1)   # first kernel's start to last kernel's end, per step (HIP events)
 
     # per-slot row counts of this batch (for the byte/flop accounting of the roofline)
-    sl = mmoe.remap_permute(shape, X, vid, mmoe.route(shape, X, vid, Wr, br)[0], M, ws)
+    idx = mmoe.route(shape, X, vid, Wr, br)[0]
+    sl = mmoe.remap_permute(shape, X, vid, idx, M, ws)
     counts = sl[1].cpu().numpy()
     torch.cuda.synchronize()
     return dict(ms_per_step=wall / steps * 1e3, stages_ms=stages, counts=counts, S=S, Y=Y,
+                topk_idx=idx.cpu().numpy(), perm=sl[3].cpu().numpy(),
                 events_ms={"median": float(np.median(per_step)), "min": float(per_step.min())})
+
+
+def stage_rates(cfg, stages):
+    """Algorithmic HBM bytes of the three small stages over their measured durations (GB/s):
+    the router reads every token row once; grouping reads three and writes three integers per
+    (token, pick) pair (the fused layer makes no gathered copy of the rows); the combination
+    reads k fp32 expert-output rows per token and writes one row in the storage type."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    P = cfg.T * cfg.top_k
+    nbytes = {"route": cfg.T * cfg.d_model * es, "permute": P * 6 * 4,
+              "combine": P * cfg.d_model * 4 + cfg.T * cfg.d_model * es}
+    return {k: v / (stages[k] * 1e-3) / 1e9 for k, v in nbytes.items()}
 
 
 def roofline(cfg, res, skinny):
@@ -188,10 +203,22 @@ def roofline(cfg, res, skinny):
                 flops_per_launch=flops, avg_launch_ms=dur_s * 1e3)
 
 
-def cpu_baseline(cfg, inp, n_tokens):
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(cfg, inp, n_tokens, res):
     """The oracle as it stands, timed on this host: routing and grouping over every token,
     the expert stage and the combination over a seeded sample of tokens, extrapolated
-    linearly to the whole batch."""
+    linearly to the whole batch.  The oracle's results are then compared with what the GPU
+    produced in the timed runs: second return value, the parity block."""
     import numpy as np
 
     import oracle
@@ -201,16 +228,32 @@ def cpu_baseline(cfg, inp, n_tokens):
     n = min(n, cfg.T)
     t0 = time.perf_counter()
     idx, w, _ = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], cfg.top_k, cfg.dtype)
-    slot, *_ = oracle.remap_group(inp["vid"], idx, inp["M"], int(inp["S"]))
+    slot, _, _, perm, _ = oracle.remap_group(inp["vid"], idx, inp["M"], int(inp["S"]))
     t_route = time.perf_counter() - t0
     toks = np.sort(np.random.default_rng(0).choice(cfg.T, n, replace=False))
     t0 = time.perf_counter()
-    oracle.layer_tokens(inp, cfg.top_k, cfg.dtype, cfg.act, toks, routed=(idx, w, slot))
+    Y_ref = oracle.layer_tokens(inp, cfg.top_k, cfg.dtype, cfg.act, toks, routed=(idx, w, slot))
     t_ffn = time.perf_counter() - t0
     est = t_route + t_ffn * cfg.T / n
-    return dict(value=cfg.T / est, unit="tokens/s", cores=threads, kind="oracle",
+    base = dict(value=cfg.T / est, unit="tokens/s", cores=threads, cpu=cpu_model(), kind="oracle",
                 sample=f"routing+grouping on all {cfg.T} tokens ({t_route:.2f} s); expert FFN+combine on {n} "
                        f"seeded tokens ({t_ffn:.2f} s), extrapolated linearly to {cfg.T}")
+    # parity of the timed GPU path with the oracle: integer outputs on every token, the layer's
+    # output on the sampled tokens, to the tolerance the tests use
+    import torch
+
+    got = res["Y"][torch.from_numpy(toks).cuda()].float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - Y_ref)
+    if cfg.dtype == "bf16":
+        bound, tol = 1e-2 + 2e-2 * np.abs(Y_ref), "|d| <= 1e-2 + 2e-2 |ref|"
+    else:
+        rms = float(np.sqrt(np.mean(Y_ref * Y_ref)))
+        bound, tol = 1e-4 * np.abs(Y_ref) + 1e-4 * rms, "|d| <= 1e-4 |ref| + 1e-4 rms(ref)"
+    parity = dict(selected_experts_bit_equal=bool(np.array_equal(res["topk_idx"], idx)),
+                  permutation_bit_equal=bool(np.array_equal(res["perm"], perm)),
+                  tokens=int(n), max_abs=float(err.max()), max_abs_ref=float(np.abs(Y_ref).max()),
+                  outside_tol=int((err > bound).sum()), tolerance=tol)
+    return base, parity
 
 
 def main():
@@ -265,6 +308,7 @@ def main():
                    "expert_kernels": "weight-streaming" if skinny else f"matrix-core, {tile_rows}-row tiles"},
         "layer_tflops": layer_flops / (ms * 1e-3) / 1e12,
         "stages_ms": res["stages_ms"],
+        "stages_GBps": stage_rates(cfg, res["stages_ms"]),
         "step_ms_by_events": res["events_ms"],
         "roofline": roofline(cfg, res, skinny),
     }
@@ -280,7 +324,8 @@ def main():
             "config": {"workload": dcfg.name, "T": dcfg.T, "S": S, "active_slots": active},
             "value": dcfg.T / (dms * 1e-3), "unit": "tokens/s", "ms_per_step": dms,
             "layer_gbs": active * 3 * dcfg.d_model * dcfg.d_ff * 2 / (dms * 1e-3) / 1e9,
-            "stages_ms": dres["stages_ms"], "step_ms_by_events": dres["events_ms"],
+            "stages_ms": dres["stages_ms"], "stages_GBps": stage_rates(dcfg, dres["stages_ms"]),
+            "step_ms_by_events": dres["events_ms"],
             "roofline": roofline(dcfg, dres, True),
         }
 
@@ -304,7 +349,27 @@ def main():
         del src, dst
 
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, inp, a.cpu_sample_tokens)
+        out["cpu_baseline"], out["parity"] = cpu_baseline(cfg, inp, a.cpu_sample_tokens, res)
+
+    if not a.no_second_seed and not a.zero_pool:
+        # robustness row: the same workload from another seed (another table, pool and batch)
+        del pool
+        torch.cuda.empty_cache()
+        cfg2 = cfg.replace(seed=cfg.seed + 1)
+        inp2 = synth.make_inputs(cfg2)
+        S2 = int(inp2["S"])
+        shape2 = mmoe.make_shape(cfg2.T, cfg2.d_model, cfg2.d_ff, cfg2.V, cfg2.E, S2, cfg2.top_k, cfg2.dtype, cfg2.act)
+        W1, W3, W2 = (to_dev(inp2[k]) for k in ("W1", "W3", "W2"))
+        pool2 = mmoe.pack_weights(shape2, W1, W3, W2)
+        torch.cuda.synchronize()
+        del W1, W3, W2
+        torch.cuda.empty_cache()
+        res2 = run_workload(cfg2, inp2, pool2, a.steps, a.warmup)
+        out["second_seed"] = {"seed": cfg2.seed, "S": S2, "ms_per_step": res2["ms_per_step"],
+                              "value": cfg2.T / (res2["ms_per_step"] * 1e-3), "unit": "tokens/s",
+                              "stages_ms": res2["stages_ms"],
+                              "slot_rows_min_med_max": [int(res2["counts"].min()), int(sorted(res2["counts"])[S2 // 2]),
+                                                        int(res2["counts"].max())]}
     print(json.dumps(out))
 
 

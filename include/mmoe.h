@@ -79,6 +79,12 @@ typedef struct {
     int32_t top_k;   /* experts selected per token               */
     int32_t dtype;   /* mmoe_dtype                               */
     int32_t act;     /* mmoe_act                                 */
+    int32_t tile_rows; /* tuning, normally 0: token rows per tile of the matrix-core expert kernels.
+                          0 chooses by shape: 128 rows (two workgroups per compute unit) when tiles are
+                          short-lived (d_model <= 1024, or fewer than 64 rows per slot on average), 256
+                          rows otherwise.  128 or 256 forces that height for the call.  Either height sums
+                          every output element in the same order: the results are bit-identical.  Any
+                          other value: MMOE_ERR_DIM.  Ignored by shapes that use the streaming kernels. */
 } mmoe_shape;
 
 /* Host only, pure.  Workspace (bytes) sufficient for every call below, 0 if the shape is invalid. */
@@ -217,19 +223,7 @@ int mmoe_layer_forward_events(const mmoe_shape *shape, const void *X, const int3
                               void *stream, void *const *events);
 
 /*
- * Tuning knob, host only, process-wide (not thread-safe against concurrent calls of the
- * expert stage): the number of token rows per tile of the matrix-core expert kernels.
- * 0 (the default) chooses by shape: 128 rows (two workgroups per compute unit) when tiles
- * are short-lived (d_model <= 1024, or fewer than 64 rows per slot on average), 256 rows
- * otherwise.  128
- * or 256 forces that height for every later call.  Either height sums every output
- * element in the same order, so the results are bit-identical.  Returns 0, or MMOE_ERR_DIM
- * for any other value.
- */
-int mmoe_set_expert_tile_rows(int rows);
-
-/*
- * Host only, pure (apart from reading the knob above): which expert-stage kernels
+ * Host only, pure: which expert-stage kernels
  * mmoe_expert_ffn and mmoe_layer_forward will use for this shape.  *streaming = 1: the
  * weight-streaming kernels (every fp32 shape; bf16 with few rows per slot), *tile_rows = 32
  * (rows of a slot per pass over its weights); *streaming = 0: the matrix-core kernels with

@@ -12,6 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmmoe.so")
 OBJ_DIR = os.path.join(HERE, "_build")
+TILED_ASM = os.path.join(OBJ_DIR, "ffn_tiled-hip-amdgcn-amd-amdhsa-gfx950.s")  # compiler output, device side
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -53,7 +54,10 @@ def build(verbose: bool = False, force: bool = True, jobs: int = 8) -> str:
         obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
         objs.append(obj)
         if force or not os.path.exists(obj) or os.path.getmtime(obj) < max(os.path.getmtime(src), hdr_time):
-            todo.append([HIPCC] + FLAGS + ["-c", src, "-o", obj])
+            # the matrix-core kernel keeps its assembly output (the device object is assembled from
+            # exactly that text): a test checks the written-out wait counts against it
+            keep = ["-save-temps=obj"] if os.path.basename(src) == "ffn_tiled.hip" else []
+            todo.append([HIPCC] + FLAGS + keep + ["-c", src, "-o", obj])
     with concurrent.futures.ThreadPoolExecutor(max_workers=max(1, min(jobs, len(todo) or 1))) as pool:
         list(pool.map(lambda c: _run(c, verbose), todo))
     if todo or not os.path.exists(LIB):

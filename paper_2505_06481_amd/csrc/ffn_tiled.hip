@@ -18,8 +18,6 @@
 // LDS without passing registers (global_load_lds, 16 bytes per lane) into a four-stage ring
 // of LDS tiles, [row][64 k] bf16 (128 bytes a row) with the 16-byte pieces xor-swizzled by
 // (row >> 1) & 7, two steps ahead, and are read back as fragments; one barrier per step.
-// MMOE_TILED_DMA=0 builds the earlier variant that stages token rows through registers
-// (three-stage ring, weights two steps ahead).
 //
 // Ragged groups: row ranges come from the device array `offsets`.  A one-workgroup
 // preparation kernel turns them into lists of tiles; the product kernels map their
@@ -40,12 +38,8 @@ constexpr int kBMBig = 256;    // token rows per tile: large batches (one workgr
 constexpr int kBMSmall = 128;  // token rows per tile: batches with few tiles (two workgroups per compute unit)
 constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
-#ifndef MMOE_TILED_DMA
-#define MMOE_TILED_DMA 1
-#endif
 constexpr int kXcds = 8;
-constexpr bool kDmaA = MMOE_TILED_DMA;     // token rows: global -> LDS copies without staging registers
-constexpr int kStagesA = kDmaA ? 4 : 3;    // LDS ring of token tiles
+constexpr int kStagesA = 4;    // LDS ring of token tiles
 constexpr int kLongestFirstBelow = 8 * 256;  // tiles of a product: below this, partial tiles go last
 #ifndef MMOE_TILED_NTGROUP
 #define MMOE_TILED_NTGROUP 4
@@ -230,7 +224,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
     constexpr int kThreads = kWaves * 64;
     constexpr int kNJ = BM / 32;      // 32-row token sub-tiles per wavefront (all rows of the tile)
     // 16-k slices between a weight fragment's load and its use: what the registers allow
-    constexpr int kBAhead = (kDmaA && BM == kBMBig) ? 16 : 8;
+    constexpr int kBAhead = BM == kBMBig ? 16 : 8;
     constexpr int kNP = BM * 8 / kThreads;  // 16-byte pieces of a token tile per thread
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -238,7 +232,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
     const int lr = lane & 31;
     const int wn = wave;              // which 64 weight rows of the tile
 
-    // ---- token operand: global -> registers -> LDS ----------------------------------------------
+    // ---- token operand: global -> LDS ------------------------------------------------------------
     // Piece id = i*kThreads + tid (i < kNP) of a [256 rows][8 pieces of 16 bytes] tile: 8
     // consecutive threads read one row's 128 contiguous bytes.  Rows past the end of the group
     // re-read its last row (they are multiplied but never stored).
@@ -252,15 +246,9 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
         const int r = r0 + min(row, cnt - 1);
         a_row[i] = (uint32_t)(perm ? perm[r] / kdiv : r) * (uint32_t)K * 2u;
     }
-    uint32_t a_off[kNP];
-#pragma unroll
-    for (int i = 0; i < kNP; ++i) a_off[i] = a_row[i] + (tid & 7) * 16;
-    // LDS position of piece i: row*128 + swizzled piece; (row >> 1) & 7 does not depend on i, so
-    // the positions are one register plus multiples of kThreads*16
-    const int a_lds0 = (tid >> 3) * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
-    // Copy variant: instruction i of a wavefront writes its 64 pieces to 1 KB of consecutive LDS
-    // addresses (M0 + 16*lane), 8 rows of 128 bytes, so the swizzle moves to the global side:
-    // the lane that fills physical piece q of a row fetches logical piece q ^ ((row >> 1) & 7).
+    // Copy instruction i of a wavefront writes its 64 pieces to 1 KB of consecutive LDS addresses
+    // (M0 + 16*lane), 8 rows of 128 bytes, so the swizzle is applied on the global side: the lane
+    // that fills physical piece q of a row fetches logical piece q ^ ((row >> 1) & 7).
     uint32_t a_goff[kNP];
 #pragma unroll
     for (int i = 0; i < kNP; ++i) a_goff[i] = a_row[i] + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
@@ -279,20 +267,6 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
                          : "m0", "memory");
         }
     };
-    struct ATile {
-        u32x4 v[kNP];
-    };
-    auto load_a = [&](ATile& r, int kt) {
-        const char* ab = a_base + (size_t)kt * (kBK * 2);
-#pragma unroll
-        for (int i = 0; i < kNP; ++i) r.v[i] = *reinterpret_cast<const u32x4*>(ab + a_off[i]);
-    };
-    auto store_a = [&](const ATile& r, int stage) {
-        char* base = lds_a + stage * kTileBytes;
-#pragma unroll
-        for (int i = 0; i < kNP; ++i) *reinterpret_cast<u32x4*>(base + a_lds0 + i * (kThreads * 16)) = r.v[i];
-    };
-
     // ---- weight operand: fragment-packed pool -> registers ------------------------------------------
     // A wavefront owns weight rows [64 wn, 64 wn + 64) of the tile, two 32-row blocks; for the
     // gated product they are block (n0 + 32 wn)/32 of W1 (gate) and the same block of W3 (up), so
@@ -337,8 +311,22 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
     //             reads of the step's stage have returned (only the first NJ/2 fetches of the
     //             next stage may be in flight), so nobody waits for LDS.
     // The loop is unrolled by kBAhead/4 steps so that the ring of weight registers is indexed
-    // statically.  (Register-staged variant: tokens of step t are loaded during step t-5 and
-    // written to stage t mod 3 during step t-3.)
+    // statically.
+    //
+    // What orders the copies.  The compiler does not see them, so the wait that makes them
+    // land is written out next to every barrier: s_waitcnt vmcnt(N) returns when at most N of
+    // this wavefront's vector-memory instructions are outstanding, and they complete in issue
+    // order.  Rule at every such wait: only the most recent group of kNP copies may still be in
+    // flight, every older one has landed.  That holds if at least N vector-memory instructions
+    // were issued after the last copy of the second most recent group: the kNP copies of the most
+    // recent group plus weight-fragment loads, whose place in the instruction stream the compiler
+    // chooses.  Their count is therefore not taken on trust: tests/test_tiled_wait_counts.py
+    // reads the compiler's assembly output for this file and checks the rule at every written-out
+    // wait of every instantiation, along every path that reaches it.
+    // What orders the LDS reads.  Before a stage is handed back to the copies, the fragments
+    // of that stage that are still to be used are made operands of an (empty) asm statement in
+    // front of the barrier, so the compiler itself waits for exactly those reads and for nothing
+    // younger (the NH fetches of the next stage stay in flight across the barrier).
     const int nkt = K / kBK;         // even: K is a multiple of 256
     const int last = nkt - 1;
     const int last_slice = K / 16 - 1;
@@ -376,34 +364,18 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
             __builtin_amdgcn_sched_group_barrier(0x020, NB, 0);
         };
 
-        ATile ra[2];
         BFrags bq[kBAhead];
-        if constexpr (kDmaA) {
-            // prologue: copies of steps 0..3 into the four stages, then the first weight fragments.
-            // Order matters for the written-out waits: at least 16 loads follow the copies of step
-            // 1 (the copies of steps 2 and 3), so vmcnt(16 + weight loads) leaves steps 0 and 1 landed.
-            copy_a(0, 0);
-            copy_a(1, min(1, last));
-            copy_a(2, min(2, last));
-            copy_a(3, min(3, last));
+        // prologue: copies of steps 0..3 into the four stages, then the first weight fragments;
+        // the wait leaves at most the copies of step 3 in flight
+        copy_a(0, 0);
+        copy_a(1, min(1, last));
+        copy_a(2, min(2, last));
+        copy_a(3, min(3, last));
 #pragma unroll
-            for (int g = 0; g < kBAhead; ++g) load_bf(bq[g], g);
-            static_assert(2 * kNP + NB * kBAhead <= 63, "vmcnt is a 6-bit counter");
-            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * kNP + NB * kBAhead) : "memory");
-        } else {
-            // prologue: steps 0..2 into the three stages, steps 3 and 4 on their way into registers
-            load_a(ra[0], 0);
-            load_a(ra[1], 1);
-#pragma unroll
-            for (int g = 0; g < kBAhead; ++g) load_bf(bq[g], g);
-            store_a(ra[0], 0);
-            load_a(ra[0], min(2, last));
-            store_a(ra[1], 1);
-            load_a(ra[1], min(3, last));
-            store_a(ra[0], 2);
-            load_a(ra[0], min(4, last));
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        }
+        for (int g = 0; g < kBAhead; ++g) load_bf(bq[g], g);
+        static_assert(kNP + NB * kBAhead <= 63, "vmcnt is a 6-bit counter");
+        __builtin_amdgcn_sched_barrier(0);  // the weight loads are issued before the wait, not after it
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kNP + NB * kBAhead) : "memory");
         {
             const char* p0 = frag_ptr(0, 0);
 #pragma unroll
@@ -411,8 +383,9 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
         }
 
         int st = 0;  // LDS stage of step kt
-        constexpr int kUnroll = kBAhead >= 8 ? kBAhead / 4 : 2;  // steps per trip: the weight ring is indexed statically
-        for (int kt = 0; kt < nkt; kt += kUnroll) {
+        constexpr int kUnroll = kBAhead / 4;  // steps per trip: the weight ring is indexed statically
+        int kt = 0;
+        do {  // at least one trip (K >= 256): the prologue's loads have nowhere to sink to
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int t = kt + u;
@@ -432,45 +405,38 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
                         __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
                         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     }
-                    // all reads of stage st have returned except, possibly, the NH fetches just issued,
-                    // which read the next stage
-                    if constexpr (kDmaA) {
-                        // This wavefront's copies of step t+2 were issued two steps ago, after the
-                        // barrier of step t-2 (for t < 2: in the prologue); since then it has issued
-                        // the kNP copies of step t+3 and at least 16 weight-fragment loads (2 in the
-                        // rest of that slice, 8 in step t-1, 6 in this step), so vmcnt(16) leaves them
-                        // landed: after the barrier every wavefront may read step t+2, whose first
-                        // fragments are fetched before the next barrier.
-                        static_assert(kNP + 8 * NB >= 16, "steady state: loads issued after a copy group");
-                        static_assert(kNP + NB * kBAhead + 3 * NB >= 16, "first step: after the copies of step 2");
-                        asm volatile("s_waitcnt vmcnt(16) lgkmcnt(%0)\n\ts_barrier" ::"n"(NH) : "memory");
-                        copy_a(st, min(t + 4, last));  // tokens of step t+4; past the end: a harmless reload
-                    } else {
-                        asm volatile("s_waitcnt lgkmcnt(%0)\n\ts_barrier" ::"n"(NH) : "memory");
-                        store_a(ra[(u + 1) & 1], st);  // tokens of step t+3
-                        load_a(ra[(u + 1) & 1], min(t + 5, last));
-                    }
+                    // Stage st goes back to the copies after this barrier.  Its fragments that are still
+                    // to be used (sub-tiles NH.. of this slice) become operands here, so the compiler
+                    // waits for those reads; every other read of the stage has been consumed by a matrix
+                    // instruction above.  The NH fetches just issued read the next stage and stay in flight.
+#pragma unroll
+                    for (int j = NH; j < NJ; ++j) asm volatile("" ::"v"(fa[j]));
+                    // This wavefront's copies of step t+2 were issued two steps ago, after the barrier of
+                    // step t-2 (for t < 2: in the prologue); since then it has issued the kNP copies of
+                    // step t+3 and, in the order written here, 16 weight-fragment loads (2 in the rest of
+                    // that slice, 8 in step t-1, 6 in this step): vmcnt(16) leaves the copies of step t+2
+                    // landed, and after the barrier every wavefront may read that step, whose first
+                    // fragments are fetched before the next barrier.
+                    static_assert(kNP + 8 * NB >= 16, "steady state: loads issued after a copy group");
+                    static_assert(kNP + NB * kBAhead + 3 * NB >= 16, "first step: after the copies of step 2");
+                    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+                    copy_a(st, min(t + 4, last));  // tokens of step t+4; past the end: a harmless reload
 #pragma unroll
                     for (int j = NH; j < NJ; ++j) mma_roll(j, fb, next);
                     load_bf(fb, g + kBAhead + 3);
 #pragma unroll
-                    for (int q = 0; q < (kNP > NJ - NH ? kNP : NJ - NH); ++q) {
-                        if (q < NJ - NH) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        }
-                        if (!kDmaA && q < kNP) {
-                            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                        }
+                    for (int q = 0; q < NJ - NH; ++q) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     }
                     __builtin_amdgcn_sched_group_barrier(0x020, NB, 0);
                 }
                 st = stn;
             }
-        }
+            kt += kUnroll;
+        } while (kt < nkt);
         // no copy may still be on its way into LDS when the epilogue reuses it or the workgroup ends
-        if constexpr (kDmaA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
     switch (min(kNJ, (cnt + 31) / 32)) {  // uniform over the workgroup
         case 8: if constexpr (kNJ >= 8) run(std::integral_constant<int, 8>{}); break;
@@ -553,18 +519,9 @@ static void tiled_nts(const mmoe_shape& s, int& nt_up, int& nt_down)
 // height forced: on the Switch shape (d = 768) 128 rows win at every batch size up to 16384
 // tokens; on the Mixtral shape (d = 4096) they win up to 59 rows per slot (384 tokens) and
 // lose from 79 rows per slot (512 tokens) on.
-static int g_tile_rows = 0;  // 0: by shape; 128 or 256: forced (mmoe_set_expert_tile_rows)
-
-int set_tile_rows(int rows)
-{
-    if (rows != 0 && rows != kBMSmall && rows != kBMBig) return MMOE_ERR_DIM;
-    g_tile_rows = rows;
-    return MMOE_OK;
-}
-
 int planned_tile_rows(const mmoe_shape& s)
 {
-    if (g_tile_rows) return g_tile_rows;
+    if (s.tile_rows) return s.tile_rows;  // forced for this call (checked by check_shape: 128 or 256)
     const int64_t P = (int64_t)s.T * s.top_k;
     return (s.d_model <= 1024 || P < (int64_t)64 * s.S) ? kBMSmall : kBMBig;
 }

@@ -13,12 +13,15 @@ int check_shape(const mmoe_shape* s)
         return MMOE_ERR_DIM;
     if (s->dtype != MMOE_F32 && s->dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     if (s->act != MMOE_RELU && s->act != MMOE_SWIGLU) return MMOE_ERR_DTYPE;
+    if (s->tile_rows != 0 && s->tile_rows != 128 && s->tile_rows != 256) return MMOE_ERR_DIM;
     if (s->top_k > s->E || s->top_k > kMaxTopK) return MMOE_ERR_TOPK;
     if (s->d_model % 256 != 0 || s->d_ff % 256 != 0) return MMOE_ERR_MULTIPLE;
     if (s->E > kMaxE || s->S > kMaxS) return MMOE_ERR_LIMIT;
     int64_t P = (int64_t)s->T * s->top_k;
     int64_t widest = s->d_model > s->d_ff ? s->d_model : s->d_ff;
     if (P > (int64_t)1 << 30 || P * widest >= ((int64_t)1 << 35)) return MMOE_ERR_LIMIT;
+    // the matrix-core expert kernels address a panel with 32-bit byte offsets
+    if (!use_skinny(*s) && P * widest >= ((int64_t)1 << 31)) return MMOE_ERR_LIMIT;
     return MMOE_OK;
 }
 
@@ -267,8 +270,6 @@ int mmoe_layer_forward_static(const mmoe_shape* shape, const void* X, const int3
     return mmoe_layer_forward_events(shape, X, vid, Wr, br, M, W1p, W3p, W2p, Y, ws,
                                      (size_t)MMOE_STATIC_WORKSPACE_BYTES, stream, nullptr);
 }
-
-int mmoe_set_expert_tile_rows(int rows) { return mmoe::set_tile_rows(rows); }
 
 int mmoe_expert_plan(const mmoe_shape* shape, int* streaming, int* tile_rows)
 {

@@ -66,7 +66,6 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
                      hipStream_t st, hipEvent_t mid = nullptr);
 size_t tiled_table_bytes(const mmoe_shape& s);
-int set_tile_rows(int rows);
 int planned_tile_rows(const mmoe_shape& s);  // tile height launch_ffn_tiled would use for this shape
 int launch_combine(const mmoe_shape& s, const float* Yg, const int32_t* inv_perm, const float* topk_w,
                    void* Y, hipStream_t st);

@@ -26,7 +26,7 @@ _TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
 EXPORTS = [
     "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
     "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_layer_forward_events",
-    "mmoe_layer_forward_static", "mmoe_validate_inputs", "mmoe_set_expert_tile_rows", "mmoe_probe_ceilings", "mmoe_expert_plan",
+    "mmoe_layer_forward_static", "mmoe_validate_inputs", "mmoe_probe_ceilings", "mmoe_expert_plan",
 ]
 
 
@@ -38,13 +38,14 @@ class MmoeError(RuntimeError):
 
 class Shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("T", "d_model", "d_ff", "V", "E", "S", "top_k", "dtype", "act")]
+                ("T", "d_model", "d_ff", "V", "E", "S", "top_k", "dtype", "act", "tile_rows")]
 
 
-def make_shape(T, d_model, d_ff, V, E, S, top_k, dtype, act) -> Shape:
+def make_shape(T, d_model, d_ff, V, E, S, top_k, dtype, act, tile_rows=0) -> Shape:
+    """``tile_rows``: tuning field of the matrix-core expert kernels, 0 = chosen by shape."""
     dt = _DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
     ac = _ACTS[act] if isinstance(act, str) else int(act)
-    return Shape(T, d_model, d_ff, V, E, S, top_k, dt, ac)
+    return Shape(T, d_model, d_ff, V, E, S, top_k, dt, ac, tile_rows)
 
 
 _lib = None
@@ -74,7 +75,6 @@ def lib():
         L.mmoe_layer_forward_events.argtypes = [sp] + [vp] * 10 + [sz, vp, vp]
         L.mmoe_layer_forward_static.argtypes = [sp] + [vp] * 10
         L.mmoe_validate_inputs.argtypes = [sp, vp, vp, vp, sz, vp]
-        L.mmoe_set_expert_tile_rows.argtypes = [i]
         L.mmoe_expert_plan.argtypes = [sp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.mmoe_probe_ceilings.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_float), vp]
         for n in EXPORTS[2:]:
@@ -234,11 +234,6 @@ def validate_inputs(shape: Shape, vid, M, ws) -> bool:
     if rc < 0:
         raise MmoeError(rc, "mmoe_validate_inputs")
     return rc == 0
-
-
-def set_expert_tile_rows(rows: int) -> None:
-    """Tuning knob of the matrix-core expert kernels: 0 = by shape, 128 or 256 = forced."""
-    _check(lib().mmoe_set_expert_tile_rows(int(rows)), "mmoe_set_expert_tile_rows")
 
 
 def probe_ceilings(gib: int = 4):

@@ -28,12 +28,13 @@ def bits(t):
 class DeviceCase:
     """One workload resident on the GPU, pool packed once (not part of any timed region)."""
 
-    def __init__(self, cfg, inp=None):
+    def __init__(self, cfg, inp=None, tile_rows=0):
         self.cfg = cfg
         self.inp = inp if inp is not None else synth.make_inputs(cfg)
         i = self.inp
         self.S = int(i["S"])
-        self.shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, self.S, cfg.top_k, cfg.dtype, cfg.act)
+        self.shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, self.S, cfg.top_k, cfg.dtype, cfg.act,
+                                     tile_rows=tile_rows)
         dt = cfg.dtype
         self.X, self.Wr = to_dev(i["X"], dt), to_dev(i["Wr"], dt)
         self.vid = torch.from_numpy(i["vid"]).cuda()

@@ -5,8 +5,8 @@ permutation, gathered rows) must match bit for bit; floating-point outputs withi
     bf16 storage:  |got - ref| <= 1e-2 + 2e-2 |ref|
     fp32 storage:  |got - ref| <= 1e-4 |ref| + 1e-4 rms(ref)
 
-Small cases compare every element; the full benchmark shapes compare every integer output
-and a seeded sample of output rows.
+Small cases compare every element; the full benchmark shapes compare every integer output,
+every row of the smallest and the largest slot, and 512 seeded tokens.
 """
 import numpy as np
 import pytest
@@ -31,11 +31,11 @@ def gc():
     return gpu_common
 
 
-def staged_vs_oracle(mm, gc, oracle, cfg, inp=None):
+def staged_vs_oracle(mm, gc, oracle, cfg, inp=None, tile_rows=0):
     """Run the four stages one by one through the C ABI and compare each with the oracle."""
     print(f"case {cfg.name} T={cfg.T} d={cfg.d_model} f={cfg.d_ff} V={cfg.V} E={cfg.E} k={cfg.top_k} "
           f"{cfg.dtype} {cfg.act} seed={cfg.seed}", flush=True)
-    case = gc.DeviceCase(cfg, inp)
+    case = gc.DeviceCase(cfg, inp, tile_rows=tile_rows)
     inp, sh, dt = case.inp, case.shape, cfg.dtype
     ref = oracle.layer_forward(inp, cfg.top_k, dt, cfg.act)
 
@@ -98,11 +98,7 @@ def test_small_cases_every_stage(mm, gc, oracle, cfg):
 def test_both_tile_heights(mm, gc, oracle, cfg, rows):
     """The matrix-core kernels at a forced tile height (by shape these small batches would only
     ever get the 128-row tiles): every stage against the oracle, ragged last tiles of 1..8 sub-tiles."""
-    mm.set_expert_tile_rows(rows)
-    try:
-        staged_vs_oracle(mm, gc, oracle, cfg)
-    finally:
-        mm.set_expert_tile_rows(0)
+    staged_vs_oracle(mm, gc, oracle, cfg, tile_rows=rows)
 
 
 def test_edge_cases(mm, gc, oracle):
@@ -180,8 +176,8 @@ def test_benchmark_shapes_full_parity(mm, gc, oracle, name):
                                        ("mixtral_prefill_bf16_v2_t8192", 1)])
 def test_benchmark_shapes_sampled_parity(mm, gc, oracle, name, seed):
     """Full-size layers in the benchmark's launch configuration: integer outputs on every
-    token, outputs on a seeded sample of rows (including rows of the smallest and the
-    largest slot) that the oracle evaluates one by one."""
+    token; expert outputs on every row of the smallest and of the largest slot; layer outputs
+    on 512 seeded tokens that the oracle evaluates one by one."""
     cfg = synth.CONFIGS[name].replace(seed=seed)
     print(f"case {name} seed {seed}: generating", flush=True)
     case = gc.DeviceCase(cfg)
@@ -200,19 +196,28 @@ def test_benchmark_shapes_sampled_parity(mm, gc, oracle, name, seed):
     assert np.array_equal(gc.bits(Xg), inp["X"][perm_ref // cfg.top_k])
     print("slot counts min/median/max:", counts_ref.min(), int(np.median(counts_ref)), counts_ref.max(), flush=True)
 
+    # staged expert stage and combination, then the fused entry point: bit-equal to each other
+    Yg = mm.expert_ffn(sh, Xg, offsets, case.W1p, case.W3p, case.W2p, case.ws)
+    Ys = mm.combine(sh, Yg, inv, w)
     Y = case.forward()
     torch.cuda.synchronize()
     assert torch.isfinite(Y.float()).all()
-    rng = np.random.default_rng(7)
+    assert torch.equal(Y, Ys), "fused entry point differs from the staged path"
+
+    # every row of the smallest and of the largest slot, one expert evaluation each
     smallest, largest = int(np.argmin(np.where(counts_ref > 0, counts_ref, 1 << 30))), int(np.argmax(counts_ref))
-    toks = set(rng.choice(cfg.T, 20, replace=False).tolist())
     for s in (smallest, largest):
-        rows = perm_ref[offsets_ref[s]:offsets_ref[s + 1]]
-        toks.update((rows[[0, len(rows) // 2, -1]] // cfg.top_k).tolist())   # first, middle, last row of the slot
-    toks = sorted(toks)
-    print(f"expert oracle on {len(toks)} sampled tokens", flush=True)
+        r0, r1 = int(offsets_ref[s]), int(offsets_ref[s + 1])
+        print(f"expert oracle on all {r1 - r0} rows of slot {s}", flush=True)
+        rows = np.arange(r0, r1)
+        Yg_ref = oracle.ffn_rows(inp["X"], (perm_ref[rows] // cfg.top_k).astype(np.int32),
+                                 np.full(r1 - r0, s, np.int32), inp["W1"], inp["W3"], inp["W2"], cfg.dtype, cfg.act)
+        gc.assert_close(gc.to_np64(Yg[r0:r1]), Yg_ref, cfg.dtype, f"Yg (all rows of slot {s})")
+    # a seeded sample of tokens through the whole layer
+    toks = np.sort(np.random.default_rng(7).choice(cfg.T, 512, replace=False))
+    print(f"layer oracle on {len(toks)} sampled tokens", flush=True)
     Y_ref = oracle.layer_tokens(inp, cfg.top_k, cfg.dtype, cfg.act, toks, routed=(idx_ref, w_ref, slot_ref))
-    gc.assert_close(gc.to_np64(Y[toks]), Y_ref, cfg.dtype, "Y (sampled)")
+    gc.assert_close(gc.to_np64(Y[torch.from_numpy(toks).cuda()]), Y_ref, cfg.dtype, "Y (sampled)")
 
 
 def test_limits_many_slots_and_widest_router(mm, gc, oracle):

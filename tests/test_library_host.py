@@ -58,6 +58,10 @@ def test_bad_arguments_become_error_codes(mm):
     assert route(mm.make_shape(4, 256, 256, 1, 300, 2, 1, "f32", "relu")) == -9          # E limit
     assert route(mm.make_shape(4, 256, 256, 1, 2, 5000, 1, "f32", "relu")) == -9         # S limit
     assert route(ok, X=ctypes.c_void_p(4100)) == -7                                      # alignment
+    # the 2^31 limit of the matrix-core expert path is a property of the shape: refused by every entry
+    # point before anything is launched, and the workspace size of such a shape is 0
+    huge = mm.make_shape(100000, 4096, 14336, 2, 8, 12, 2, "bf16", "swiglu")
+    assert route(huge) == -9 and mm.workspace_bytes(huge) == 0
     # expert stage: W3 must match the activation; workspace must be large enough
     gated = mm.make_shape(4, 256, 256, 1, 2, 2, 1, "bf16", "swiglu")
     assert L.mmoe_expert_ffn(ctypes.byref(gated), p, p, p, none, p, p, p, 1 << 30, none) == -5
@@ -89,13 +93,14 @@ def test_binding_refuses_host_tensors(mm):
         mm.route(sh, torch.zeros(4, 256), torch.zeros(4, dtype=torch.int32), torch.zeros(1, 2, 256))
 
 
-def test_tile_rows_knob_accepts_only_its_three_values(mm):
-    L = mm.lib()
+def test_tile_rows_field_accepts_only_its_three_values(mm):
     for good in (128, 256, 0):
-        assert L.mmoe_set_expert_tile_rows(good) == 0
+        assert mm.workspace_bytes(mm.make_shape(512, 256, 256, 1, 2, 2, 1, "bf16", "relu", tile_rows=good)) > 0
+    p = ctypes.c_void_p(4096)
     for bad in (64, 512, -1, 100):
-        assert L.mmoe_set_expert_tile_rows(bad) == -2
-    assert L.mmoe_set_expert_tile_rows(0) == 0
+        sh = mm.make_shape(512, 256, 256, 1, 2, 2, 1, "bf16", "relu", tile_rows=bad)
+        assert mm.workspace_bytes(sh) == 0
+        assert mm.lib().mmoe_route(ctypes.byref(sh), p, p, p, None, p, p, None) == -2
 
 
 def test_probe_rejects_bad_arguments_before_touching_the_gpu(mm):
@@ -111,9 +116,10 @@ def test_probe_rejects_bad_arguments_before_touching_the_gpu(mm):
 def test_expert_plan_follows_the_documented_dispatch(mm):
     from paper_2505_06481_amd import synth
 
-    def plan(name_or_cfg, S):
+    def plan(name_or_cfg, S, tile_rows=0):
         c = synth.CONFIGS[name_or_cfg] if isinstance(name_or_cfg, str) else name_or_cfg
-        return mm.expert_plan(mm.make_shape(c.T, c.d_model, c.d_ff, c.V, c.E, S, c.top_k, c.dtype, c.act))
+        return mm.expert_plan(mm.make_shape(c.T, c.d_model, c.d_ff, c.V, c.E, S, c.top_k, c.dtype, c.act,
+                                            tile_rows=tile_rows))
 
     assert plan("switch8_fp32_v2_t128", 12) == (True, 32)            # fp32 always streams
     assert plan("mixtral_decode_bf16_v2_t64", 13) == (True, 32)      # 10 rows per slot
@@ -125,9 +131,7 @@ def test_expert_plan_follows_the_documented_dispatch(mm):
     assert plan(mix.replace(T=105), 13) == (False, 128)              # beyond: matrix-core kernels, small tiles
     assert plan(mix.replace(T=415), 13) == (False, 128)              # under 64 rows per slot
     assert plan(mix.replace(T=416), 13) == (False, 256)
-    mm.set_expert_tile_rows(128)
-    try:
-        assert plan("mixtral_prefill_bf16_v2_t8192", 13) == (False, 128)   # the knob overrides the height only
-        assert plan("mixtral_decode_bf16_v2_t64", 13) == (True, 32)
-    finally:
-        mm.set_expert_tile_rows(0)
+    # the tuning field overrides the tile height only, and only for the call it is passed to
+    assert plan("mixtral_prefill_bf16_v2_t8192", 13, tile_rows=128) == (False, 128)
+    assert plan("mixtral_decode_bf16_v2_t64", 13, tile_rows=128) == (True, 32)
+    assert plan("mixtral_prefill_bf16_v2_t8192", 13) == (False, 256)

@@ -271,6 +271,34 @@ def test_token_shuffle_equivariance(oracle):
     assert np.array_equal(got["counts"], base["counts"])
 
 
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_contract_summation_order_selects_what_exact_logits_select(oracle, name):
+    """The fp32 summation order of the router logit is part of the written contract because it
+    decides integer outputs.  Diagnostic for the five benchmark workloads: the experts selected
+    from the contract-order fp32 logits are the ones selected from float64 logits (a library
+    matrix product of the exactly widened inputs), on every token; the smallest gap at the
+    top-k boundary is printed and must dwarf what fp32 summation can move a logit by."""
+    cfg = synth.CONFIGS[name]
+    inp = synth.make_inputs(cfg, weights=False)
+    idx, _, logits = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], cfg.top_k, cfg.dtype)
+    X, Wr = as_f64(inp["X"], cfg.dtype), as_f64(inp["Wr"], cfg.dtype)
+    exact = np.empty((cfg.T, cfg.E))
+    for v in range(cfg.V):
+        rows = np.nonzero(inp["vid"] == v)[0]
+        exact[rows] = X[rows] @ Wr[v].T
+        if inp["br"] is not None:
+            exact[rows] += inp["br"][v].astype(np.float64)
+    order = np.argsort(-exact, axis=1, kind="stable")          # descending logit, ties to the lower index
+    assert np.array_equal(order[:, :cfg.top_k], idx), "contract-order picks differ from exact-logit picks"
+    srt = np.take_along_axis(exact, order, axis=1)
+    margin = (srt[:, cfg.top_k - 1] - srt[:, cfg.top_k]).min() if cfg.E > cfg.top_k else np.inf
+    within = np.abs(np.diff(srt[:, :cfg.top_k], axis=1)).min() if cfg.top_k > 1 else np.inf
+    noise = np.abs(logits.astype(np.float64) - exact).max()
+    print(f"{name}: min top-k boundary margin {margin:.3e}, min gap between picks {within:.3e}, "
+          f"max |fp32 contract logit - exact| {noise:.3e}")
+    assert min(margin, within) > 4 * noise
+
+
 def test_ties_go_to_the_lower_expert_index(oracle):
     d, E = 16, 6
     rng = np.random.default_rng(4)
