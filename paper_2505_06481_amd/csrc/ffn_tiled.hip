@@ -40,11 +40,7 @@ constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
 constexpr int kXcds = 8;
 constexpr int kStagesA = 4;    // LDS ring of token tiles
-constexpr int kLongestFirstBelow = 8 * 256;  // tiles of a product: below this, partial tiles go last
-#ifndef MMOE_TILED_NTGROUP
-#define MMOE_TILED_NTGROUP 4
-#endif
-constexpr int kNtGroup = MMOE_TILED_NTGROUP;  // feature tiles whose workgroups start back to back on the same token panel
+constexpr int kNtGroup = 4;  // least number of feature tiles whose workgroups start back to back on the same token panel
 
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -56,20 +52,24 @@ __device__ __forceinline__ float silu_mul_t(float g, float u)
     return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
 }
 
-// Tile lists written by tile_table_kernel, one workgroup, from the device-side `offsets`:
-//   tab[0]                      number of row tiles, sum_s ceil(count_s / tile height)
-//   four lists of int4 entries  {slot, feature tile within the XCD, first row, rows valid},
-//   one per (product, feature tiles per XCD): a product with NT feature tiles gives XCD x
-//   the tiles nt with nt mod 8 == x, that is ceil or floor of NT/8 of them; list entry
-//   `local` is the tile that the workgroup with id 8*local + x computes.  A product with many
-//   tiles per compute unit lists them in the order (slot, group of kNtGroup feature tiles, row
-//   tile, feature tile within the group): workgroups start in id order a few microseconds
-//   apart, so the ones that share a token panel and the ones that share a weight panel both
-//   run close enough in time to find the panel in L2.  A product with
-//   few tiles per compute unit (fewer than kLongestFirstBelow tiles in all) lists the longest
-//   work first: every full tile in that order, and after them the partial last tiles
-//   of the slots, those with the most rows first, so that the short ones fill the end of the
-//   launch.
+// Tile lists written by tile_table_kernel, one workgroup, from the device-side `offsets`.
+//
+// Row tiles.  A slot with c rows is u = ceil(c / 32) sub-tiles of 32 rows.  It is cut into
+// mt = ceil(u / upt) tiles (upt = sub-tiles of a full tile: 8 or 4) whose heights differ by at
+// most one sub-tile: the first u mod mt tiles have floor(u / mt) + 1 sub-tiles, the others
+// floor(u / mt).  No slot has a short last tile (a tile of one sub-tile streams its weight panel
+// for an eighth of the arithmetic), and no matrix instruction is spent on padding beyond the last
+// partial sub-tile.
+//
+// Order.  tab[0] = number of row tiles; four lists of int4 entries {slot, feature tile within
+// the XCD, first row, rows}, one per (product, feature tiles per XCD): a product with NT feature
+// tiles gives XCD x the tiles nt with nt mod 8 == x, that is ceil or floor of NT/8 of them; list
+// entry `local` is the tile that the workgroup with id 8*local + x computes.  Entries are listed
+// by (slot, group of feature tiles, row tile, feature tile within the group): workgroups start
+// in id order, so the ones that share a token panel and the ones that share a weight panel run
+// close enough in time to find the panel in L2.  The group is sized so that the workgroups
+// resident on an XCD at one time form a block of row tiles x feature tiles that is as square as
+// the slot allows (8 x 4 for a slot of 8 row tiles, 4 x 8 for one of 4).
 struct TileLists {
     int hdr;        // int32 index of tab[0]
     int list[2][2]; // [product: up, down][0: ceil(NT/8) per XCD, 1: floor] -> int4 index into tab
@@ -100,90 +100,67 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
 {
     __shared__ int cnt_s[kMaxS];       // rows of each slot
     __shared__ int off_s[kMaxS];       // first row of each slot
-    __shared__ int base[kMaxS + 1];    // first full row tile of each slot (prefix sum of count / 256)
-    __shared__ int base_all[kMaxS + 1];  // first row tile of each slot, partial tiles included
-    __shared__ int ragged[kMaxS];      // slots with a partial last tile, most rows first
-    __shared__ int n_ragged;
-    const int bm_log2 = 31 - __clz(bm);  // the tile height is a power of two: shifts, not divisions, in the serial part
-    for (int s = threadIdx.x; s < S; s += 256) {
+    __shared__ int base[kMaxS + 1];    // row tiles of the slots before each slot
+    __shared__ int part[256];
+    const int tid = threadIdx.x;
+    const int upt = bm / 32;                   // sub-tiles of a full tile
+    const int conc = bm == kBMBig ? 32 : 64;   // workgroups resident on one XCD
+    for (int s = tid; s < S; s += 256) {
         const int o = offsets[s];
         off_s[s] = o;
         cnt_s[s] = offsets[s + 1] - o;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        // counting sort of the partial tiles by occupied 32-row sub-tiles, 8 down to 1
-        int bucket[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-        int run = 0, run_all = 0;
-        for (int s = 0; s < S; ++s) {
-            base[s] = run;
-            base_all[s] = run_all;
-            run += cnt_s[s] >> bm_log2;
-            run_all += (cnt_s[s] + bm - 1) >> bm_log2;
-            const int rem = cnt_s[s] & (bm - 1);
-            if (rem) ++bucket[(rem + 31) / 32];
-        }
-        base[S] = run;
-        base_all[S] = run_all;
-        int at = 0;
-        for (int b = 8; b >= 1; --b) {
-            const int c = bucket[b];
-            bucket[b] = at;
-            at += c;
-        }
-        n_ragged = at;
-        for (int s = 0; s < S; ++s) {
-            const int rem = cnt_s[s] & (bm - 1);
-            if (rem) ragged[bucket[(rem + 31) / 32]++] = s;
-        }
-        tab[L.hdr] = run + at;
+    // exclusive prefix sum of the row tiles per slot: a run of slots per thread, then a scan of the runs
+    auto tiles_of = [&](int s) { return (((cnt_s[s] + 31) >> 5) + upt - 1) / upt; };
+    const int chunk = (S + 255) / 256;
+    const int s_lo = min(tid * chunk, S), s_hi = min(s_lo + chunk, S);
+    int mine = 0;
+    for (int s = s_lo; s < s_hi; ++s) mine += tiles_of(s);
+    part[tid] = mine;
+    __syncthreads();
+    for (int dlt = 1; dlt < 256; dlt <<= 1) {
+        const int add = tid >= dlt ? part[tid - dlt] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    int run = part[tid] - mine;
+    for (int s = s_lo; s < s_hi; ++s) {
+        base[s] = run;
+        run += tiles_of(s);
+    }
+    const int total_m = part[255];
+    if (tid == 0) {
+        base[S] = total_m;
+        tab[L.hdr] = total_m;
     }
     __syncthreads();
-    const int total_full = base[S], nr = n_ragged, total_m = base_all[S];
     int4* lists = reinterpret_cast<int4*>(tab);
     for (int p = 0; p < 2; ++p) {
         const int NT = p == 0 ? nt_up : nt_down;
-        // few tiles per compute unit: the end of the launch decides, longest work first;
-        // many: keep the partial tile next to the full tiles that share its weight panel
-        const bool longest_first = total_m * NT < kLongestFirstBelow;
         for (int c = 0; c < 2; ++c) {
             if (c == 1 && NT % kXcds == 0) break;  // every XCD has the same number of feature tiles: one list
             const int nt_x = c == 0 ? (NT + kXcds - 1) / kXcds : NT / kXcds;
-            const int n_full = longest_first ? total_full * nt_x : 0, n = total_m * nt_x;
-            for (int e = threadIdx.x; e < n; e += 256) {
-                int4 ent;
-                if (!longest_first) {
-                    int lo = 0, hi = S;  // largest s with base_all[s]*nt_x <= e (empty slots have equal bounds)
-                    while (hi - lo > 1) {
-                        int mid = (lo + hi) >> 1;
-                        if (base_all[mid] * nt_x <= e) lo = mid; else hi = mid;
-                    }
-                    const int s = lo, mt_s = base_all[s + 1] - base_all[s];
-                    const int rem = e - base_all[s] * nt_x;
-                    // groups of kNtGroup feature tiles; inside a group the feature tile runs fastest
-                    const int grp = rem / (kNtGroup * mt_s), within = rem % (kNtGroup * mt_s);
-                    const int g_sz = min(kNtGroup, nt_x - grp * kNtGroup);
-                    const int mi = within / g_sz, ntl = grp * kNtGroup + within % g_sz;
-                    ent = make_int4(s, ntl, off_s[s] + mi * bm, min(bm, cnt_s[s] - mi * bm));
-                } else if (e < n_full) {
-                    int lo = 0, hi = S;  // largest s with base[s]*nt_x <= e (slots without full tiles have equal bounds)
-                    while (hi - lo > 1) {
-                        int mid = (lo + hi) >> 1;
-                        if (base[mid] * nt_x <= e) lo = mid; else hi = mid;
-                    }
-                    const int s = lo, mt_s = base[s + 1] - base[s];
-                    const int rem = e - base[s] * nt_x;
-                    const int grp = rem / (kNtGroup * mt_s), within = rem % (kNtGroup * mt_s);
-                    const int g_sz = min(kNtGroup, nt_x - grp * kNtGroup);
-                    const int mi = within / g_sz, ntl = grp * kNtGroup + within % g_sz;
-                    ent = make_int4(s, ntl, off_s[s] + mi * bm, bm);
-                } else {
-                    const int q = e - n_full;
-                    const int s = ragged[q / nt_x];
-                    const int full = cnt_s[s] >> bm_log2;
-                    ent = make_int4(s, q % nt_x, off_s[s] + full * bm, cnt_s[s] - full * bm);
+            const int n = total_m * nt_x;
+            for (int e = tid; e < n; e += 256) {
+                int lo = 0, hi = S;  // largest s with base[s]*nt_x <= e (empty slots have equal bounds)
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (base[mid] * nt_x <= e) lo = mid; else hi = mid;
                 }
-                lists[L.list[p][c] + e] = ent;
+                const int s = lo, mt = base[s + 1] - base[s];
+                const int rem = e - base[s] * nt_x;
+                // groups of g feature tiles; inside a group the feature tile runs fastest
+                const int g = min(nt_x, max(kNtGroup, conc / mt));
+                const int grp = rem / (g * mt), within = rem - grp * (g * mt);
+                const int g_sz = min(g, nt_x - grp * g);
+                const int i = within / g_sz, ntl = grp * g + within - i * g_sz;
+                // row tile i of the slot: the first `extra` tiles are one sub-tile taller
+                const int u = (cnt_s[s] + 31) >> 5, h = u / mt, extra = u - h * mt;
+                const int row0 = 32 * (i * h + min(i, extra));
+                const int rows = 32 * (h + (i < extra ? 1 : 0));
+                lists[L.list[p][c] + e] = make_int4(s, ntl, off_s[s] + row0, min(rows, cnt_s[s] - row0));
             }
         }
     }
