@@ -70,6 +70,10 @@ def parse():
                          "(nothing toggles in the multipliers): separates the chip's power limit from the "
                          "kernels' cycle efficiency; the result is not a benchmark figure")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = 96 tokens per oracle thread")
+    ap.add_argument("--decode-sweep", action="store_true",
+                    help="after the main workload (Mixtral-shaped pools only): the layer at 1, 2, 4, ... 64 tokens on "
+                         "the same pool, with the weight bytes of the slots each batch touches and the fraction of "
+                         "HBM peak over the whole layer")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference point for HBM byte counters)")
     return ap.parse_args()
@@ -114,7 +118,12 @@ class HipEvents:
 
 
 def run_workload(cfg, inp, pool, steps, warmup):
-    """Upload (pool already packed on the device), warm up, time `steps` layer passes."""
+    """Upload (pool already packed on the device), warm up, then two passes of `steps` layer
+    forwards each.  Timed pass: the host clock around all steps, and inside every step two HIP
+    events around the dominant kernel (the experts' up product) on the launch stream: the
+    roofline's launch duration comes from the timed region itself.  Breakdown pass: the same
+    launches with an event after every stage (an event record costs about 3 us of stream time,
+    as much as one of the small kernels, so the five extra ones stay out of the timed pass)."""
     import numpy as np
     import torch
 
@@ -130,23 +139,28 @@ def run_workload(cfg, inp, pool, steps, warmup):
     W1p, W3p, W2p = pool
     NE = mmoe.NUM_EVENTS
     events = HipEvents(NE * steps)
+    vp = ctypes.c_void_p
 
-    def step(i=None):
+    def step(i=None, only=None):
         ev = None
         if i is not None:
-            ev = ctypes.cast(ctypes.byref(events.ev, i * NE * ctypes.sizeof(ctypes.c_void_p)),
-                             ctypes.POINTER(ctypes.c_void_p))
+            ev = (vp * NE)(*[events.ev[i * NE + s] if only is None or s in only else None for s in range(NE)])
         mmoe.layer_forward(shape, X, vid, Wr, br, M, W1p, W3p, W2p, ws, Y=Y, events=ev)
 
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    around_up = (mmoe.EV_PERMUTE, mmoe.EV_FFN_UP)
     t0 = time.perf_counter()
+    for i in range(steps):
+        step(i, only=around_up)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    up_ms = np.array([events.elapsed_ms(i * NE + around_up[0], i * NE + around_up[1]) for i in range(steps)])
+
     for i in range(steps):
         step(i)
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
     stage_ms = np.zeros((steps, NE - 1))
     for i in range(steps):
         for s in range(NE - 1):
@@ -161,7 +175,7 @@ def run_workload(cfg, inp, pool, steps, warmup):
     sl = mmoe.remap_permute(shape, X, vid, idx, M, ws)
     counts = sl[1].cpu().numpy()
     torch.cuda.synchronize()
-    return dict(ms_per_step=wall / steps * 1e3, stages_ms=stages, counts=counts, S=S, Y=Y,
+    return dict(ms_per_step=wall / steps * 1e3, up_ms=float(up_ms.mean()), stages_ms=stages, counts=counts, S=S, Y=Y,
                 topk_idx=idx.cpu().numpy(), perm=sl[3].cpu().numpy(),
                 events_ms={"median": float(np.median(per_step)), "min": float(per_step.min())})
 
@@ -184,7 +198,7 @@ def roofline(cfg, res, skinny):
     nw = 2 if cfg.act == "swiglu" else 1
     es = 2 if cfg.dtype == "bf16" else 4
     P = cfg.T * k
-    dur_s = res["stages_ms"]["ffn_up"] * 1e-3
+    dur_s = res["up_ms"] * 1e-3     # HIP events around the kernel, in every step of the timed pass
     if skinny:
         # weight streaming: every slot with at least one row reads its nw [f, d] matrices once
         active = int((res["counts"] > 0).sum())
@@ -328,6 +342,26 @@ def main():
             "step_ms_by_events": dres["events_ms"],
             "roofline": roofline(dcfg, dres, True),
         }
+
+    if a.decode_sweep:
+        # single-request decode is the paper's own workload (section 4: one request at a time, one
+        # token per step); the layer's cost is then the weights of the few slots the batch touches
+        base = synth.CONFIGS["mixtral_decode_bf16_v2_t64"] if cfg.d_model == 4096 else cfg
+        sweep = []
+        for T in (1, 2, 4, 8, 16, 32, 64):
+            scfg = base.replace(name=f"{base.name}_T{T}", T=T, seed=cfg.seed, V=cfg.V, vid_mode="uniform",
+                                bias_alpha=0.0)
+            sinp = synth.make_inputs(scfg, weights=False)
+            assert (sinp["M"] == inp["M"]).all()
+            sres = run_workload(scfg, sinp, pool, max(a.steps, 200), a.warmup)
+            active = int((sres["counts"] > 0).sum())
+            nbytes = active * (3 if scfg.act == "swiglu" else 2) * scfg.d_model * scfg.d_ff * 2
+            ms = sres["ms_per_step"]
+            sweep.append({"T": T, "active_slots": active, "ms_per_step": ms, "weight_bytes": nbytes,
+                          "layer_GBps": nbytes / (ms * 1e-3) / 1e9,
+                          "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                          "stages_ms": sres["stages_ms"]})
+        out["decode_sweep"] = sweep
 
     if not a.no_ceilings:
         # what this GPU delivers with nothing else in the way: a pure streaming read and a pure

@@ -205,8 +205,9 @@ int mmoe_layer_forward_static(const mmoe_shape *shape, const void *X, const int3
  * enabled; events[MMOE_EV_START] is recorded on `stream` before the first kernel and
  * events[i] right after the last kernel of stage i, so that the elapsed time between two
  * consecutive events is the duration of one stage (the expert stage is split into its up
- * product + activation and its down product: one kernel each).  NULL `events` makes this
- * identical to mmoe_layer_forward.  The results do not depend on `events`.
+ * product + activation and its down product: one kernel each).  A NULL entry is skipped (a
+ * caller that wants one kernel's duration passes the two events around it); NULL `events`
+ * makes this identical to mmoe_layer_forward.  The results do not depend on `events`.
  */
 enum {
     MMOE_EV_START = 0,

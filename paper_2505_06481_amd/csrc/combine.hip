@@ -20,7 +20,8 @@ __global__ __launch_bounds__(kCombThreads) void combine_kernel(const f32x4* __re
 #pragma unroll
     for (int j = 0; j < kMaxTopK; ++j)
         if (j < k) {
-            rows[j] = inv_perm[(size_t)t * k + j];
+            // without a permutation the expert outputs are indexed by pair id (self-grouping expert stage)
+            rows[j] = inv_perm ? inv_perm[(size_t)t * k + j] : t * k + j;
             w[j] = topk_w[(size_t)t * k + j];
         }
     for (int c = threadIdx.x; c < d4; c += kCombThreads) {

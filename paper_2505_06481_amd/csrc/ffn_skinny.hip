@@ -11,6 +11,12 @@
 // In the fused layer the token rows of the first product are read through the grouping
 // permutation (row perm[r] / top_k of X) instead of from a gathered copy.
 //
+// Self-grouping mode (decode-sized batches of the fused layer): no grouping kernel runs at
+// all.  The router has written slot[p] for every pair; a workgroup collects the pairs of its
+// slot itself, in ascending pair id (which is the stable order of the grouped form), and the
+// intermediates H and Yg are indexed by pair id instead of by grouped row.  Every row is still
+// summed in the same order, so the layer's output is bit-identical to the staged path's.
+//
 // fp32 kernel (skinny_kernel): transposed pool [S, N, K], 16 features per workgroup,
 // 16x16x4 matrix instructions, two 16-row token blocks per pass.  Reduction-index
 // permutation: per 256-byte step of a row, lane group g = lane/16 loads the contiguous 64
@@ -44,21 +50,74 @@ template <> struct Mma<float> {  // fp32, 16x16x4: one 16-byte piece = 4 element
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
 
+constexpr int kSelfMaxP = 1024;  // most pairs for which the expert kernels group by themselves
+
+// Rows of one slot.  Grouped form: rows [r0, r0 + cnt) of the grouped order; input row of grouped
+// row r is r itself, or perm[r] / kdiv (gather folded into the loads).  Self-grouping form: the
+// pairs p with slot_of_pair[p] == s, ascending, collected here into `mine` by the first
+// wavefront (ballot + popcount ranks); input row p / kdiv, output row p.
+struct RowSet {
+    int r0, cnt;
+    const int32_t* perm;
+    int kdiv;
+    const int* mine;  // LDS list of pair ids, or null in the grouped form
+    __device__ __forceinline__ int in_row(int rr) const
+    {
+        if (mine) return mine[rr] / kdiv;
+        return perm ? perm[r0 + rr] / kdiv : r0 + rr;
+    }
+    __device__ __forceinline__ int out_row(int rr) const { return mine ? mine[rr] : r0 + rr; }
+};
+
+__device__ __forceinline__ RowSet slot_rows(const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
+                                            int kdiv, const int32_t* __restrict__ slot_of_pair, int P, int s,
+                                            int* mine, int* mine_cnt)
+{
+    RowSet rs;
+    rs.perm = perm;
+    rs.kdiv = kdiv;
+    rs.mine = nullptr;
+    if (!slot_of_pair) {
+        rs.r0 = offsets[s];
+        rs.cnt = offsets[s + 1] - rs.r0;
+        return rs;
+    }
+    if (threadIdx.x < kWave) {
+        int n = 0;
+        for (int p0 = 0; p0 < P; p0 += kWave) {
+            const int p = p0 + threadIdx.x;
+            const bool hit = p < P && slot_of_pair[p] == s;
+            const unsigned long long m = __ballot(hit);
+            if (hit) mine[n + __popcll(m & ((1ull << threadIdx.x) - 1ull))] = p;
+            n += __popcll(m);
+        }
+        if (threadIdx.x == 0) *mine_cnt = n;
+    }
+    __syncthreads();
+    rs.r0 = 0;
+    rs.cnt = *mine_cnt;
+    rs.mine = mine;
+    return rs;
+}
+
 template <typename T, int NW, int KU, int MODE>
 __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict__ A,
                                                             const int32_t* __restrict__ perm, int kdiv,
                                                             const int32_t* __restrict__ offsets,
+                                                            const int32_t* __restrict__ slot_of_pair, int P,
                                                             const T* __restrict__ W0, const T* __restrict__ W1,
                                                             void* __restrict__ out, int K, int N)
 {
     constexpr int EPB = 16 / (int)sizeof(T);  // elements per 16-byte piece
     constexpr int KSS = 16 * EPB;             // elements per 256-byte step
     __shared__ float red[kSkWaves][kSkMB][NW][kWave][4];
+    __shared__ int mine[kSelfMaxP];
+    __shared__ int mine_cnt;
 
     const int s = blockIdx.y;
     const int n0 = blockIdx.x * 16;
-    const int r0 = offsets[s];
-    const int cnt = offsets[s + 1] - r0;
+    const RowSet rs = slot_rows(offsets, perm, kdiv, slot_of_pair, P, s, mine, &mine_cnt);
+    const int cnt = rs.cnt;
     if (cnt <= 0) return;  // uniform over the workgroup
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -76,8 +135,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
 #pragma unroll
         for (int mb = 0; mb < kSkMB; ++mb) {
             int rr = min(pass0 + mb * 16 + li, cnt - 1);  // rows past the end re-read the last one; never stored
-            const int r = perm ? perm[r0 + rr] / kdiv : r0 + rr;  // gather folded into the loads
-            arow[mb] = A + (size_t)r * K + g * (4 * EPB);
+            arow[mb] = A + (size_t)rs.in_row(rr) * K + g * (4 * EPB);
         }
         f32x4 acc[kSkMB][NW];
 #pragma unroll
@@ -164,7 +222,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
                     else if (MODE == kModeReluH) o[i] = fmaxf(v[0][i], 0.0f);
                     else o[i] = v[0][i];
                 }
-                const size_t at = (size_t)(r0 + row) * N + n0 + 4 * (l >> 4);
+                const size_t at = (size_t)rs.out_row(row) * N + n0 + 4 * (l >> 4);
                 if (MODE == kModePlainF32 || sizeof(T) == 4) {
                     *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = f32x4{o[0], o[1], o[2], o[3]};
                 } else {
@@ -191,16 +249,19 @@ template <int NW, int KU, int MODE>
 __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t* __restrict__ A,
                                                                  const int32_t* __restrict__ perm, int kdiv,
                                                                  const int32_t* __restrict__ offsets,
+                                                                 const int32_t* __restrict__ slot_of_pair, int P,
                                                                  const uint16_t* __restrict__ W0,
                                                                  const uint16_t* __restrict__ W1,
                                                                  void* __restrict__ out, int K, int N)
 {
     __shared__ float red[kSkWaves][NW][kWave][16];  // 16 KB per matrix
+    __shared__ int mine[kSelfMaxP];
+    __shared__ int mine_cnt;
 
     const int s = blockIdx.y;
     const int nb = blockIdx.x;
-    const int r0 = offsets[s];
-    const int cnt = offsets[s + 1] - r0;
+    const RowSet rs = slot_rows(offsets, perm, kdiv, slot_of_pair, P, s, mine, &mine_cnt);
+    const int cnt = rs.cnt;
     if (cnt <= 0) return;  // uniform over the workgroup
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -216,8 +277,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
 
     for (int pass0 = 0; pass0 < cnt; pass0 += 32) {
         const int rr = min(pass0 + tok, cnt - 1);  // tokens past the end re-read the last one; never stored
-        const int r = perm ? perm[r0 + rr] / kdiv : r0 + rr;  // gather folded into the loads
-        const uint16_t* arow = A + (size_t)r * K + h * 32;
+        const uint16_t* arow = A + (size_t)rs.in_row(rr) * K + h * 32;
         f32x16 acc[NW];
 #pragma unroll
         for (int w = 0; w < NW; ++w)
@@ -294,7 +354,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
                     else if (MODE == kModeReluH) o[i] = fmaxf(v[0], 0.0f);
                     else o[i] = v[0];
                 }
-                const size_t at = (size_t)(r0 + row) * N + nb * 32 + 8 * q + 4 * (l >> 5);
+                const size_t at = (size_t)rs.out_row(row) * N + nb * 32 + 8 * q + 4 * (l >> 5);
                 if (MODE == kModePlainF32) {
                     *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = f32x4{o[0], o[1], o[2], o[3]};
                 } else {
@@ -310,54 +370,61 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
 }
 
 static int run_skinny_bf16(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
-                           const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
+                           const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
                            hipEvent_t mid)
 {
     const int32_t* noperm = nullptr;
-    const int d = s.d_model, f = s.d_ff;
+    const int d = s.d_model, f = s.d_ff, P = s.T * s.top_k;
     dim3 block(kSkThreads);
     dim3 g1(f / 32, s.S), g2(d / 32, s.S);
     const uint16_t* nul = nullptr;
     if (s.act == MMOE_SWIGLU)
         hipLaunchKernelGGL((skinny_frag_kernel<2, 1, kModeSwigluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
-                           s.top_k, offsets, (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f);
+                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f);
     else
         hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeReluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
-                           s.top_k, offsets, (const uint16_t*)W1p, nul, H, d, f);
+                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
     hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModePlainF32>), g2, block, 0, st, (const uint16_t*)H, noperm, 1,
-                       offsets, (const uint16_t*)W2p, nul, (void*)Yg, f, d);
+                       offsets, slot_of_pair, P, (const uint16_t*)W2p, nul, (void*)Yg, f, d);
     return launch_status();
 }
 
 template <typename T>
 static int run_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
-                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
+                      const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
                       hipEvent_t mid)
 {
     const int32_t* noperm = nullptr;
-    const int d = s.d_model, f = s.d_ff;
+    const int d = s.d_model, f = s.d_ff, P = s.T * s.top_k;
     dim3 block(kSkThreads);
     dim3 g1(f / 16, s.S), g2(d / 16, s.S);
     const T* nul = nullptr;
     if (s.act == MMOE_SWIGLU)
         hipLaunchKernelGGL((skinny_kernel<T, 2, 1, kModeSwigluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
-                           offsets, (const T*)W1p, (const T*)W3p, H, d, f);
+                           offsets, slot_of_pair, P, (const T*)W1p, (const T*)W3p, H, d, f);
     else
         hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
-                           offsets, (const T*)W1p, nul, H, d, f);
+                           offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
     hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModePlainF32>), g2, block, 0, st, (const T*)H, noperm, 1,
-                       offsets, (const T*)W2p, nul, (void*)Yg, f, d);
+                       offsets, slot_of_pair, P, (const T*)W2p, nul, (void*)Yg, f, d);
     return launch_status();
 }
 
-int launch_ffn_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
-                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
-                      hipEvent_t mid)
+bool self_grouping(const mmoe_shape& s)
 {
-    if (s.dtype == MMOE_BF16) return run_skinny_bf16(s, rows, perm, offsets, W1p, W3p, W2p, H, Yg, st, mid);
-    return run_skinny<float>(s, rows, perm, offsets, W1p, W3p, W2p, H, Yg, st, mid);
+    return use_skinny(s) && (int64_t)s.T * s.top_k <= kSelfMaxP;
+}
+
+int launch_ffn_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
+                      const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H,
+                      float* Yg, hipStream_t st, hipEvent_t mid)
+{
+    if (slot_of_pair && (int64_t)s.T * s.top_k > kSelfMaxP) return MMOE_ERR_LIMIT;
+    if (s.dtype == MMOE_BF16)
+        return run_skinny_bf16(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid);
+    return run_skinny<float>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid);
 }
 
 }  // namespace mmoe

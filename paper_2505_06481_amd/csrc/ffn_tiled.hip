@@ -29,18 +29,15 @@
 #include <type_traits>
 
 #include "mmoe_internal.h"
+#include "tile_table.h"
 
 namespace mmoe {
 
 enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2 };
 
-constexpr int kBMBig = 256;    // token rows per tile: large batches (one workgroup per compute unit)
-constexpr int kBMSmall = 128;  // token rows per tile: batches with few tiles (two workgroups per compute unit)
 constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
-constexpr int kXcds = 8;
 constexpr int kStagesA = 4;    // LDS ring of token tiles
-constexpr int kNtGroup = 4;  // least number of feature tiles whose workgroups start back to back on the same token panel
 
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -52,118 +49,11 @@ __device__ __forceinline__ float silu_mul_t(float g, float u)
     return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
 }
 
-// Tile lists written by tile_table_kernel, one workgroup, from the device-side `offsets`.
-//
-// Row tiles.  A slot with c rows is u = ceil(c / 32) sub-tiles of 32 rows.  It is cut into
-// mt = ceil(u / upt) tiles (upt = sub-tiles of a full tile: 8 or 4) whose heights differ by at
-// most one sub-tile: the first u mod mt tiles have floor(u / mt) + 1 sub-tiles, the others
-// floor(u / mt).  No slot has a short last tile (a tile of one sub-tile streams its weight panel
-// for an eighth of the arithmetic), and no matrix instruction is spent on padding beyond the last
-// partial sub-tile.
-//
-// Order.  tab[0] = number of row tiles; four lists of int4 entries {slot, feature tile within
-// the XCD, first row, rows}, one per (product, feature tiles per XCD): a product with NT feature
-// tiles gives XCD x the tiles nt with nt mod 8 == x, that is ceil or floor of NT/8 of them; list
-// entry `local` is the tile that the workgroup with id 8*local + x computes.  Entries are listed
-// by (slot, group of feature tiles, row tile, feature tile within the group): workgroups start
-// in id order, so the ones that share a token panel and the ones that share a weight panel run
-// close enough in time to find the panel in L2.  The group is sized so that the workgroups
-// resident on an XCD at one time form a block of row tiles x feature tiles that is as square as
-// the slot allows (8 x 4 for a slot of 8 row tiles, 4 x 8 for one of 4).
-struct TileLists {
-    int hdr;        // int32 index of tab[0]
-    int list[2][2]; // [product: up, down][0: ceil(NT/8) per XCD, 1: floor] -> int4 index into tab
-    int cap[2];     // entries reserved per list of each product
-    size_t bytes;
-};
-
-static TileLists tile_lists(int P, int S, int nt_up, int nt_down, int bm)
-{
-    TileLists L;
-    const int mt = (P + bm - 1) / bm + S;  // upper bound of the number of row tiles
-    L.hdr = 0;
-    L.cap[0] = mt * ((nt_up + kXcds - 1) / kXcds);
-    L.cap[1] = mt * ((nt_down + kXcds - 1) / kXcds);
-    int at = 16;  // int4 units; the header takes the first 256 bytes
-    for (int p = 0; p < 2; ++p)
-        for (int c = 0; c < 2; ++c) {
-            L.list[p][c] = at;
-            at += L.cap[p];
-        }
-    L.bytes = (size_t)at * 16;
-    return L;
-}
-
 __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restrict__ offsets,
                                                          int32_t* __restrict__ tab, int S, int nt_up, int nt_down,
                                                          int bm, TileLists L)
 {
-    __shared__ int cnt_s[kMaxS];       // rows of each slot
-    __shared__ int off_s[kMaxS];       // first row of each slot
-    __shared__ int base[kMaxS + 1];    // row tiles of the slots before each slot
-    __shared__ int part[256];
-    const int tid = threadIdx.x;
-    const int upt = bm / 32;                   // sub-tiles of a full tile
-    const int conc = bm == kBMBig ? 32 : 64;   // workgroups resident on one XCD
-    for (int s = tid; s < S; s += 256) {
-        const int o = offsets[s];
-        off_s[s] = o;
-        cnt_s[s] = offsets[s + 1] - o;
-    }
-    __syncthreads();
-    // exclusive prefix sum of the row tiles per slot: a run of slots per thread, then a scan of the runs
-    auto tiles_of = [&](int s) { return (((cnt_s[s] + 31) >> 5) + upt - 1) / upt; };
-    const int chunk = (S + 255) / 256;
-    const int s_lo = min(tid * chunk, S), s_hi = min(s_lo + chunk, S);
-    int mine = 0;
-    for (int s = s_lo; s < s_hi; ++s) mine += tiles_of(s);
-    part[tid] = mine;
-    __syncthreads();
-    for (int dlt = 1; dlt < 256; dlt <<= 1) {
-        const int add = tid >= dlt ? part[tid - dlt] : 0;
-        __syncthreads();
-        part[tid] += add;
-        __syncthreads();
-    }
-    int run = part[tid] - mine;
-    for (int s = s_lo; s < s_hi; ++s) {
-        base[s] = run;
-        run += tiles_of(s);
-    }
-    const int total_m = part[255];
-    if (tid == 0) {
-        base[S] = total_m;
-        tab[L.hdr] = total_m;
-    }
-    __syncthreads();
-    int4* lists = reinterpret_cast<int4*>(tab);
-    for (int p = 0; p < 2; ++p) {
-        const int NT = p == 0 ? nt_up : nt_down;
-        for (int c = 0; c < 2; ++c) {
-            if (c == 1 && NT % kXcds == 0) break;  // every XCD has the same number of feature tiles: one list
-            const int nt_x = c == 0 ? (NT + kXcds - 1) / kXcds : NT / kXcds;
-            const int n = total_m * nt_x;
-            for (int e = tid; e < n; e += 256) {
-                int lo = 0, hi = S;  // largest s with base[s]*nt_x <= e (empty slots have equal bounds)
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (base[mid] * nt_x <= e) lo = mid; else hi = mid;
-                }
-                const int s = lo, mt = base[s + 1] - base[s];
-                const int rem = e - base[s] * nt_x;
-                // groups of g feature tiles; inside a group the feature tile runs fastest
-                const int g = min(nt_x, max(kNtGroup, conc / mt));
-                const int grp = rem / (g * mt), within = rem - grp * (g * mt);
-                const int g_sz = min(g, nt_x - grp * g);
-                const int i = within / g_sz, ntl = grp * g + within - i * g_sz;
-                // row tile i of the slot: the first `extra` tiles are one sub-tile taller
-                const int u = (cnt_s[s] + 31) >> 5, h = u / mt, extra = u - h * mt;
-                const int row0 = 32 * (i * h + min(i, extra));
-                const int rows = 32 * (h + (i < extra ? 1 : 0));
-                lists[L.list[p][c] + e] = make_int4(s, ntl, off_s[s] + row0, min(rows, cnt_s[s] - row0));
-            }
-        }
-    }
+    build_tile_lists(offsets, tab, S, nt_up, nt_down, bm, L);
 }
 
 template <int MODE, int BM>
@@ -533,9 +423,19 @@ static void launch_tiled_products(const mmoe_shape& s, const TileLists& L, const
                        (const uint16_t*)W2p, nul, (void*)Yg, f, d, nt_down);
 }
 
+TileJob tile_job(const mmoe_shape& s, int32_t* tab)
+{
+    TileJob j;
+    j.tab = tab;
+    tiled_nts(s, j.nt_up, j.nt_down);
+    j.bm = planned_tile_rows(s);
+    j.L = tile_lists(s.T * s.top_k, s.S, j.nt_up, j.nt_down, j.bm);
+    return j;
+}
+
 int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
-                     hipStream_t st, hipEvent_t mid)
+                     hipStream_t st, hipEvent_t mid, bool tab_ready)
 {
     if (s.dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     const int P = s.T * s.top_k, d = s.d_model, f = s.d_ff;
@@ -544,7 +444,8 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
     tiled_nts(s, nt_up, nt_down);
     const int bm = planned_tile_rows(s);
     const TileLists L = tile_lists(P, s.S, nt_up, nt_down, bm);
-    hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, bm, L);
+    if (!tab_ready)
+        hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, bm, L);
     bool event_failed = false;
     if (bm == kBMBig)
         launch_tiled_products<kBMBig>(s, L, rows, perm, W1p, W3p, W2p, H, Yg, tab, nt_up, nt_down, st, mid,

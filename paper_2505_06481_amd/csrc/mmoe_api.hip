@@ -159,7 +159,7 @@ int mmoe_expert_ffn(const mmoe_shape* shape, const void* Xg, const int32_t* offs
         misaligned(W2p, 16) || misaligned(Yg, 16) || misaligned(offsets, 4))
         return MMOE_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    if (use_skinny(*shape)) return launch_ffn_skinny(*shape, Xg, nullptr, offsets, W1p, W3p, W2p, ws, Yg, st);
+    if (use_skinny(*shape)) return launch_ffn_skinny(*shape, Xg, nullptr, offsets, nullptr, W1p, W3p, W2p, ws, Yg, st);
     return launch_ffn_tiled(*shape, Xg, nullptr, offsets, W1p, W3p, W2p, ws, Yg, (int32_t*)((char*)ws + h_bytes),
                             st);
 }
@@ -192,7 +192,7 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
         return MMOE_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     auto mark = [&](int i) -> int {
-        if (!events) return MMOE_OK;
+        if (!events || !events[i]) return MMOE_OK;
         return hipEventRecord((hipEvent_t)events[i], st) == hipSuccess ? MMOE_OK : MMOE_ERR_LAUNCH;
     };
     char* w = (char*)ws;
@@ -201,23 +201,37 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
     int32_t* offsets = (int32_t*)(w + L.offsets);
     int32_t* inv_perm = (int32_t*)(w + L.inv_perm);
     float* Yg = (float*)(w + L.Yg);
-    hipEvent_t mid = events ? (hipEvent_t)events[MMOE_EV_FFN_UP] : nullptr;
+    hipEvent_t mid = events ? (hipEvent_t)events[MMOE_EV_FFN_UP] : nullptr;  // may be null
 
     if ((rc = mark(MMOE_EV_START))) return rc;
+    if (self_grouping(*shape)) {
+        // Decode-sized batches: four launches.  The router looks the picks up in the expert map, the
+        // expert kernels collect the pairs of their slot themselves and index H and Yg by pair id, the
+        // combination reads them by pair id: no grouping kernel, bit-identical output.
+        int32_t* slot = (int32_t*)(w + L.slot);
+        if ((rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st, M, slot))) return rc;
+        if ((rc = mark(MMOE_EV_ROUTE))) return rc;
+        if ((rc = mark(MMOE_EV_PERMUTE))) return rc;
+        if ((rc = launch_ffn_skinny(*shape, X, nullptr, nullptr, slot, W1p, W3p, W2p, w + L.H, Yg, st, mid))) return rc;
+        if ((rc = mark(MMOE_EV_FFN_DOWN))) return rc;
+        if ((rc = launch_combine(*shape, Yg, nullptr, topk_w, Y, st))) return rc;
+        return mark(MMOE_EV_COMBINE);
+    }
     if ((rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st))) return rc;
     if ((rc = mark(MMOE_EV_ROUTE))) return rc;
     // no gathered copy of the token rows: the up product reads X through perm
     int32_t* perm = (int32_t*)(w + L.perm);
+    const bool tiled = !use_skinny(*shape);
+    int32_t* tile_tab = (int32_t*)(w + L.tile_tab);
     rc = launch_permute(*shape, X, vid, topk_idx, M, (int32_t*)(w + L.slot), (int32_t*)(w + L.counts), offsets,
                         perm, inv_perm, nullptr, (int32_t*)(w + L.blk_counts), (int32_t*)(w + L.blk_base), L.nblk,
-                        st);
+                        st, tiled ? tile_tab : nullptr);
     if (rc) return rc;
     if ((rc = mark(MMOE_EV_PERMUTE))) return rc;
-    if (use_skinny(*shape))
-        rc = launch_ffn_skinny(*shape, X, perm, offsets, W1p, W3p, W2p, w + L.H, Yg, st, mid);
+    if (!tiled)
+        rc = launch_ffn_skinny(*shape, X, perm, offsets, nullptr, W1p, W3p, W2p, w + L.H, Yg, st, mid);
     else
-        rc = launch_ffn_tiled(*shape, X, perm, offsets, W1p, W3p, W2p, w + L.H, Yg, (int32_t*)(w + L.tile_tab), st,
-                              mid);
+        rc = launch_ffn_tiled(*shape, X, perm, offsets, W1p, W3p, W2p, w + L.H, Yg, tile_tab, st, mid, true);
     if (rc) return rc;
     if ((rc = mark(MMOE_EV_FFN_DOWN))) return rc;
     if ((rc = launch_combine(*shape, Yg, inv_perm, topk_w, Y, st))) return rc;

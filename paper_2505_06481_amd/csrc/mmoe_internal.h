@@ -48,25 +48,36 @@ int check_shape(const mmoe_shape* s);
 bool use_skinny(const mmoe_shape& s);
 
 // Kernel launchers (one per translation unit).  All return an mmoe_status.
+// `M` and `slot` both given: the router also writes slot[p] = M[vid[t]][topk_idx[p]] (step M).
 int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const void* Wr, const float* br,
-                 int32_t* topk_idx, float* topk_w, hipStream_t st);
+                 int32_t* topk_idx, float* topk_w, hipStream_t st, const int32_t* M = nullptr,
+                 int32_t* slot = nullptr);
 // `Xg` null: everything but the row gather (the fused layer reads token rows through `perm`).
+// `tile_tab` given: the kernel that finishes the grouping also writes the tile lists of the
+// matrix-core expert kernels there (launch_ffn_tiled is then called with tab_ready).
 int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const int32_t* topk_idx,
                    const int32_t* M, int32_t* slot, int32_t* counts, int32_t* offsets, int32_t* perm,
                    int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk,
-                   hipStream_t st);
+                   hipStream_t st, int32_t* tile_tab = nullptr);
 // Expert stage.  Row r of the grouped input is rows[r] when `perm` is null (rows = Xg), and
 // rows[perm[r] / top_k] otherwise (rows = X: the gather is folded into the up product's loads).
 // `mid`, when not null, is recorded between the up product (+ activation) and the down product.
+// `slot_of_pair` given (self-grouping, only when self_grouping(s)): no grouping has run; every
+// workgroup collects the pairs of its slot from slot_of_pair[P] itself, rows = X, and H and Yg are
+// indexed by pair id; `perm` and `offsets` are then unused.
 int launch_ffn_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
-                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
-                      hipEvent_t mid = nullptr);
+                      const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H,
+                      float* Yg, hipStream_t st, hipEvent_t mid = nullptr);
+// true when the fused layer skips the grouping kernels (streaming expert kernels, few pairs)
+bool self_grouping(const mmoe_shape& s);
 // `tab`: tiled_table_bytes() of scratch for the row-tile table.
+// `tab_ready`: the grouping kernels have already written the tile lists into `tab`.
 int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
-                     hipStream_t st, hipEvent_t mid = nullptr);
+                     hipStream_t st, hipEvent_t mid = nullptr, bool tab_ready = false);
 size_t tiled_table_bytes(const mmoe_shape& s);
 int planned_tile_rows(const mmoe_shape& s);  // tile height launch_ffn_tiled would use for this shape
+// `inv_perm` null: Yg is indexed by pair id.
 int launch_combine(const mmoe_shape& s, const float* Yg, const int32_t* inv_perm, const float* topk_w,
                    void* Y, hipStream_t st);
 int launch_pack(const mmoe_shape& s, const void* W1, const void* W3, const void* W2, void* W1p, void* W3p,

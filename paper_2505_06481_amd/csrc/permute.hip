@@ -11,10 +11,12 @@
 // Work split: workgroup b owns pairs [b*2048, (b+1)*2048); inside it wavefront w owns a
 // contiguous quarter, walked 64 pairs at a time in ascending order.
 #include "mmoe_internal.h"
+#include "tile_table.h"
 
 namespace mmoe {
 
 constexpr int kPermThreads = 256;
+static_assert(kPermThreads == 256, "build_tile_lists is written for one workgroup of 256 threads");
 constexpr int kPermWaves = kPermThreads / kWave;
 constexpr int kPairsPerWave = kPermChunk / kPermWaves;  // 512
 
@@ -46,7 +48,8 @@ __global__ __launch_bounds__(kPermThreads) void slot_hist_kernel(
 __global__ __launch_bounds__(kPermThreads) void slot_scan_kernel(const int32_t* __restrict__ blk_counts,
                                                                  int32_t* __restrict__ blk_base,
                                                                  int32_t* __restrict__ counts,
-                                                                 int32_t* __restrict__ offsets, int nblk, int S)
+                                                                 int32_t* __restrict__ offsets, int nblk, int S,
+                                                                 TileJob tiles)
 {
     __shared__ int tot[kMaxS];
     __shared__ int off[kMaxS + 1];
@@ -82,6 +85,11 @@ __global__ __launch_bounds__(kPermThreads) void slot_scan_kernel(const int32_t* 
     for (int s = threadIdx.x; s < S; s += kPermThreads) {
         int o = off[s];
         for (int b = 0; b < nblk; ++b) blk_base[(size_t)b * S + s] += o;
+    }
+    // the tile lists of the matrix-core expert kernels, from the offsets this workgroup has just written
+    if (tiles.tab) {
+        __syncthreads();
+        build_tile_lists(offsets, tiles.tab, S, tiles.nt_up, tiles.nt_down, tiles.bm, tiles.L);
     }
 }
 
@@ -156,7 +164,7 @@ __global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_
 __global__ __launch_bounds__(kPermThreads) void slot_group_small_kernel(
     const int32_t* __restrict__ vid, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ M,
     int32_t* __restrict__ slot, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm, int P, int k, int V, int E, int S)
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm, int P, int k, int V, int E, int S, TileJob tiles)
 {
     __shared__ int wtot[kPermWaves][kMaxS];
     __shared__ int cursor[kPermWaves][kMaxS];
@@ -225,6 +233,10 @@ __global__ __launch_bounds__(kPermThreads) void slot_group_small_kernel(
         int s = valid ? myslot[p] : 0;
         place_pairs(cur, s, valid, lane, sbits, p, perm, inv_perm);
     }
+    if (tiles.tab) {  // uniform over the workgroup; the offsets were written before the barriers above
+        __syncthreads();
+        build_tile_lists(offsets, tiles.tab, S, tiles.nt_up, tiles.nt_down, tiles.bm, tiles.L);
+    }
 }
 
 // Xg[r,:] = X[perm[r] / k, :], one wavefront per row, 16 bytes per lane per step.
@@ -265,17 +277,19 @@ int launch_validate(const mmoe_shape& s, const int32_t* vid, const int32_t* M, i
 
 int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const int32_t* topk_idx,
                    const int32_t* M, int32_t* slot, int32_t* counts, int32_t* offsets, int32_t* perm,
-                   int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk, hipStream_t st)
+                   int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk, hipStream_t st,
+                   int32_t* tile_tab)
 {
     const int P = s.T * s.top_k;
+    const TileJob tiles = tile_job(s, tile_tab);
     if (nblk == 1)
         hipLaunchKernelGGL(slot_group_small_kernel, dim3(1), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot, counts,
-                           offsets, perm, inv_perm, P, s.top_k, s.V, s.E, s.S);
+                           offsets, perm, inv_perm, P, s.top_k, s.V, s.E, s.S, tiles);
     else {
         hipLaunchKernelGGL(slot_hist_kernel, dim3(nblk), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot,
                            blk_counts, P, s.top_k, s.V, s.E, s.S);
         hipLaunchKernelGGL(slot_scan_kernel, dim3(1), dim3(kPermThreads), 0, st, blk_counts, blk_base, counts,
-                           offsets, nblk, s.S);
+                           offsets, nblk, s.S, tiles);
         hipLaunchKernelGGL(slot_scatter_kernel, dim3(nblk), dim3(kPermThreads), 0, st, slot, blk_base, perm,
                            inv_perm, P, s.S);
     }

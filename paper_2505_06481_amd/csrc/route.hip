@@ -40,8 +40,12 @@ template <> struct Vec4<uint16_t> {
 // The k winners among E logits in LDS, found by one wavefront: lane l looks after experts
 // l, l+64, l+128, l+192; k arg-max reductions, ties to the lower index; coefficients =
 // softmax over the selected logits.
+// With a table row `map_row` (= M[vid[t]], or null) the picks are also looked up in the expert
+// map and slot[t*k + j] is written: step M folded into the router for batches whose expert stage
+// groups the pairs itself.
 __device__ __forceinline__ void select_topk(const float* __restrict__ lds_logit, int lane, int E, int k, int t,
-                                            int32_t* __restrict__ topk_idx, float* __restrict__ topk_w)
+                                            int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                            const int32_t* __restrict__ map_row, int32_t* __restrict__ slot, int S)
 {
     constexpr int kPerLane = kMaxE / kWave;
     float mine[kPerLane];
@@ -93,6 +97,8 @@ __device__ __forceinline__ void select_topk(const float* __restrict__ lds_logit,
             if (j < k) {
                 topk_idx[(size_t)t * k + j] = seli[j];
                 topk_w[(size_t)t * k + j] = z[j] / tot;
+                // the clamp keeps every later index in range even for an invalid table (results then undefined)
+                if (map_row) slot[(size_t)t * k + j] = min(max(map_row[seli[j]], 0), S - 1);
             }
     }
 }
@@ -105,7 +111,7 @@ template <typename T>
 __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     const T* __restrict__ X, const int32_t* __restrict__ vid, const T* __restrict__ Wr,
     const float* __restrict__ br, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d,
-    int V, int E, int k)
+    int V, int E, int k, const int32_t* __restrict__ M, int32_t* __restrict__ slot, int S)
 {
     __shared__ float lds_logit[kMaxE];
     const int lane = threadIdx.x & (kWave - 1);
@@ -148,7 +154,7 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     __syncthreads();
     if (wave != 0) return;
 
-    select_topk(lds_logit, lane, E, k, t, topk_idx, topk_w);
+    select_topk(lds_logit, lane, E, k, t, topk_idx, topk_w, M ? M + (size_t)v * E : nullptr, slot, S);
 }
 
 // Four consecutive elements as loaded (bf16 stays packed until it is used, which halves the
@@ -181,7 +187,7 @@ template <typename T, int NC>
 __global__ __launch_bounds__(kRouteTokWaves* kWave) void route_token_kernel(
     const T* __restrict__ X, const int32_t* __restrict__ vid, const T* __restrict__ Wr,
     const float* __restrict__ br, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d,
-    int V, int E, int k)
+    int V, int E, int k, const int32_t* __restrict__ M, int32_t* __restrict__ slot, int S)
 {
     __shared__ float lds_logit[kRouteTokWaves][kMaxE];
     const int lane = threadIdx.x & (kWave - 1);
@@ -235,11 +241,11 @@ __global__ __launch_bounds__(kRouteTokWaves* kWave) void route_token_kernel(
     // program order, the fence keeps the compiler from moving them
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    select_topk(mylogit, lane, E, k, t, topk_idx, topk_w);
+    select_topk(mylogit, lane, E, k, t, topk_idx, topk_w, M ? M + (size_t)v * E : nullptr, slot, S);
 }
 
 int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const void* Wr, const float* br,
-                 int32_t* topk_idx, float* topk_w, hipStream_t st)
+                 int32_t* topk_idx, float* topk_w, hipStream_t st, const int32_t* M, int32_t* slot)
 {
     // Large batches of a common hidden size: a wavefront per token (the token row is read
     // once); otherwise a workgroup per token (lower latency, any d).
@@ -251,10 +257,10 @@ int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const v
     case NC:                                                                                                        \
         if (s.dtype == MMOE_BF16)                                                                                   \
             hipLaunchKernelGGL((route_token_kernel<uint16_t, NC>), grid, block, 0, st, (const uint16_t*)X, vid,     \
-                               (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k);       \
+                               (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S);       \
         else                                                                                                        \
             hipLaunchKernelGGL((route_token_kernel<float, NC>), grid, block, 0, st, (const float*)X, vid,           \
-                               (const float*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k);          \
+                               (const float*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S);          \
         break
         switch (nc) {
             MMOE_ROUTE_TOK(1);
@@ -272,10 +278,10 @@ int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const v
     dim3 grid(s.T), block(kRouteWaves * kWave);
     if (s.dtype == MMOE_BF16)
         hipLaunchKernelGGL(route_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)X, vid,
-                           (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k);
+                           (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S);
     else
         hipLaunchKernelGGL(route_kernel<float>, grid, block, 0, st, (const float*)X, vid, (const float*)Wr, br,
-                           topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k);
+                           topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S);
     return launch_status();
 }
 

@@ -191,7 +191,7 @@ EV_START, EV_ROUTE, EV_PERMUTE, EV_FFN_UP, EV_FFN_DOWN, EV_COMBINE = range(NUM_E
 
 
 def layer_forward(shape: Shape, X, vid, Wr, br, M, W1p, W3p, W2p, ws, Y=None, events=None):
-    """``events``: optional ctypes array of NUM_EVENTS hipEvent_t handles (c_void_p)."""
+    """``events``: optional ctypes array of NUM_EVENTS hipEvent_t handles (c_void_p); null entries are skipped."""
     dt = _TORCH_DT[shape.dtype]
     S, d, f = shape.S, shape.d_model, shape.d_ff
     if Y is None:

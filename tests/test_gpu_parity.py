@@ -220,6 +220,33 @@ def test_benchmark_shapes_sampled_parity(mm, gc, oracle, name, seed):
     gc.assert_close(gc.to_np64(Y[torch.from_numpy(toks).cuda()]), Y_ref, cfg.dtype, "Y (sampled)")
 
 
+def test_decode_sizes_one_to_sixty_four_tokens(mm, gc, oracle):
+    """Single-request decode is the paper's own workload (section 4).  The Mixtral-shaped layer at
+    1, 2, 4, ... 64 tokens on one pool: the fused entry point (four launches, the expert kernels
+    group the pairs themselves) against the oracle on every token, bit-equal to the staged calls
+    and to itself on a second run."""
+    cfg64 = synth.CONFIGS["mixtral_decode_bf16_v2_t64"]
+    case = gc.DeviceCase(cfg64)
+    for T in (1, 2, 4, 8, 16, 32, 64):
+        print(f"decode T={T}", flush=True)
+        cfg = cfg64.replace(T=T)
+        sh = mm.make_shape(T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, case.S, cfg.top_k, cfg.dtype, cfg.act)
+        inp = dict(case.inp, X=case.inp["X"][:T], vid=case.inp["vid"][:T])
+        X, vid = case.X[:T].contiguous(), case.vid[:T].contiguous()
+        ref = oracle.layer_forward(inp, cfg.top_k, cfg.dtype, cfg.act)
+        Y = mm.layer_forward(sh, X, vid, case.Wr, case.br, case.M, case.W1p, case.W3p, case.W2p, case.ws)
+        torch.cuda.synchronize()
+        gc.assert_close(gc.to_np64(Y), ref["Y"], cfg.dtype, f"Y at T={T}")
+        idx, w = mm.route(sh, X, vid, case.Wr, case.br)
+        slot, counts, offsets, perm, inv, Xg = mm.remap_permute(sh, X, vid, idx, case.M, case.ws)
+        assert np.array_equal(idx.cpu().numpy(), ref["topk_idx"]) and np.array_equal(perm.cpu().numpy(), ref["perm"])
+        Ys = mm.combine(sh, mm.expert_ffn(sh, Xg, offsets, case.W1p, case.W3p, case.W2p, case.ws), inv, w)
+        Y2 = mm.layer_forward(sh, X, vid, case.Wr, case.br, case.M, case.W1p, case.W3p, case.W2p, case.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Ys), f"T={T}: fused entry point differs from the staged path"
+        assert torch.equal(Y, Y2), f"T={T}: two runs differ"
+
+
 def test_limits_many_slots_and_widest_router(mm, gc, oracle):
     """Close to the documented limits: a pool of several hundred slots (most of them empty or
     nearly empty for a small batch), and E = 256 experts with k = 8."""
