@@ -34,7 +34,8 @@ _SRC = os.path.join(_HERE, "mmoe_oracle.c")
 _LIB = os.path.join(_HERE, "libmmoe_oracle.so")
 
 DTYPE = {"f32": 0, "bf16": 1}
-ACT = {"relu": 0, "swiglu": 1}
+ACT = {"relu": 0, "swiglu": 1, "gelu": 2}
+GATE = {"selected": 0, "all": 1}
 
 
 def build(force: bool = False) -> str:
@@ -57,7 +58,7 @@ def lib():
         L = ctypes.CDLL(build())
         i, vp = ctypes.c_int, ctypes.c_void_p
         L.mmoe_oracle_threads.restype = ctypes.c_int
-        L.mmoe_oracle_route.argtypes = [i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp]
+        L.mmoe_oracle_route.argtypes = [i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp]
         L.mmoe_oracle_remap_group.argtypes = [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
         L.mmoe_oracle_gather.argtypes = [i, i, i, i, vp, vp, vp]
         L.mmoe_oracle_ffn_rows.argtypes = [i, vp, vp, i, i, i, i, vp, vp, vp, vp, vp]
@@ -88,8 +89,10 @@ def _stored(a: np.ndarray, dtype: str) -> np.ndarray:
     return np.ascontiguousarray(a)
 
 
-def route(X, vid, Wr, br, top_k: int, dtype: str):
-    """Step R.  Returns (topk_idx [T,k] int32, topk_w [T,k] float64, logits [T,E] float32)."""
+def route(X, vid, Wr, br, top_k: int, dtype: str, gate: str = "selected"):
+    """Step R.  Returns (topk_idx [T,k] int32, topk_w [T,k] float64, logits [T,E] float32).
+    ``gate``: "selected" = softmax over the k selected logits; "all" = softmax over all E
+    logits, the selected experts keeping their probabilities without renormalisation."""
     X, Wr = _stored(X, dtype), _stored(Wr, dtype)
     T, d = X.shape
     V, E, _ = Wr.shape
@@ -98,7 +101,7 @@ def route(X, vid, Wr, br, top_k: int, dtype: str):
     idx = np.empty((T, top_k), np.int32)
     w = np.empty((T, top_k), np.float64)
     logits = np.empty((T, E), np.float32)
-    lib().mmoe_oracle_route(T, d, V, E, top_k, DTYPE[dtype], _p(X), _p(vid), _p(Wr), _p(br),
+    lib().mmoe_oracle_route(T, d, V, E, top_k, DTYPE[dtype], GATE[gate], _p(X), _p(vid), _p(Wr), _p(br),
                             _p(idx), _p(w), _p(logits))
     return idx, w, logits
 
@@ -164,10 +167,10 @@ def combine(Yg, inv_perm, topk_w):
     return Y
 
 
-def layer_forward(inp: Dict, top_k: int, dtype: str, act: str) -> Dict[str, np.ndarray]:
+def layer_forward(inp: Dict, top_k: int, dtype: str, act: str, gate: str = "selected") -> Dict[str, np.ndarray]:
     """The staged layer R -> M -> G -> F -> C over every token; returns all intermediates."""
     S = int(inp["S"])
-    idx, w, logits = route(inp["X"], inp["vid"], inp["Wr"], inp["br"], top_k, dtype)
+    idx, w, logits = route(inp["X"], inp["vid"], inp["Wr"], inp["br"], top_k, dtype, gate)
     slot, counts, offsets, perm, inv = remap_group(inp["vid"], idx, inp["M"], S)
     Xg = gather(inp["X"], perm, top_k, dtype)
     Yg = expert_ffn(Xg, offsets, inp["W1"], inp["W3"], inp["W2"], dtype, act)
@@ -177,14 +180,14 @@ def layer_forward(inp: Dict, top_k: int, dtype: str, act: str) -> Dict[str, np.n
 
 
 def layer_tokens(inp: Dict, top_k: int, dtype: str, act: str, tokens: Sequence[int],
-                 routed=None) -> np.ndarray:
+                 routed=None, gate: str = "selected") -> np.ndarray:
     """Y[t,:] (float64) for the listed tokens only: the same stage functions, with the
     expert stage restricted to the rows those tokens own.  Routing and grouping run on
     every token (they are cheap); ``routed`` may pass their results in."""
     S = int(inp["S"])
     tokens = np.asarray(tokens, dtype=np.int64)
     if routed is None:
-        idx, w, _ = route(inp["X"], inp["vid"], inp["Wr"], inp["br"], top_k, dtype)
+        idx, w, _ = route(inp["X"], inp["vid"], inp["Wr"], inp["br"], top_k, dtype, gate)
         slot, *_ = remap_group(inp["vid"], idx, inp["M"], S)
     else:
         idx, w, slot = routed

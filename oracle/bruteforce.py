@@ -8,8 +8,9 @@ are evaluated with Python/numpy float64 scalars and vectors.
 
 For each token t (per-layer body of the paper's Algorithm 2): v = vid[t]; the
 variant's gate scores the E experts; the k best are taken (ties to the lower
-index); their coefficients are the softmax over the selected logits; each pick
-e goes through the table to slot M[v][e]; y = sum_j w_j * FFN_slot_j(x_t).
+index); their coefficients are the softmax over the selected logits (gate
+"selected") or their own entries of the softmax over all E logits (gate "all");
+each pick e goes through the table to slot M[v][e]; y = sum_j w_j * FFN_slot_j(x_t).
 """
 from __future__ import annotations
 
@@ -94,6 +95,8 @@ def expert(x, W1, W3, W2, act: str, bf16_h: bool):
     if act == "swiglu":
         u = x @ W3
         h = np.array([gi / (1.0 + math.exp(-gi)) * ui for gi, ui in zip(g, u)])
+    elif act == "gelu":
+        h = np.array([0.5 * gi * math.erfc(-gi / math.sqrt(2.0)) for gi in g])   # a * Phi(a), Phi by erfc
     else:
         h = np.array([gi if gi > 0.0 else 0.0 for gi in g])
     if bf16_h:
@@ -101,7 +104,7 @@ def expert(x, W1, W3, W2, act: str, bf16_h: bool):
     return h @ W2
 
 
-def layer(X, vid, Wr, br, M, W1, W3, W2, top_k: int, act: str, bf16_h: bool):
+def layer(X, vid, Wr, br, M, W1, W3, W2, top_k: int, act: str, bf16_h: bool, gate: str = "selected"):
     """X [T,d], Wr [V,E,d], W* as float arrays holding the stored values exactly.
     Returns (topk_idx [T,k], topk_w [T,k] float64, Y [T,d] float64)."""
     X = np.asarray(X, dtype=np.float64)
@@ -116,7 +119,7 @@ def layer(X, vid, Wr, br, M, W1, W3, W2, top_k: int, act: str, bf16_h: bool):
         order = sorted(range(E), key=lambda e: (-logit[e], e))[:top_k]
         m = logit[order[0]]
         z = [math.exp(logit[e] - m) for e in order]
-        tot = sum(z)
+        tot = sum(z) if gate == "selected" else math.fsum(math.exp(l - m) for l in logit)
         for j, e in enumerate(order):
             idx[t, j] = e
             wts[t, j] = z[j] / tot

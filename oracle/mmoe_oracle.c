@@ -22,10 +22,19 @@
  *     an optional fp32 bias added last;
  *   - selection: k times the largest remaining logit, ties to the lower index;
  *     picks are listed in selection order;
- *   - coefficients: softmax over the k selected logits (k = 1 gives exactly 1);
+ *   - coefficients, two readings of "the gate network generates weighted
+ *     averaging coefficients for each expert, and ... the top experts are
+ *     selected" (section 3.2).  Gate mode 0: softmax over the k selected logits
+ *     (they sum to 1; k = 1 gives exactly 1), the Mixtral-style gate.  Gate
+ *     mode 1: softmax over all E logits, each selected expert keeping its own
+ *     probability with no renormalisation (they sum to less than 1 unless
+ *     k = E), the Switch-style gate of the family the paper uses for its
+ *     scalability experiment (section 4.3);
  *   - SwiGLU expert: (silu(x W1) * (x W3)) W2, silu(a) = a / (1 + exp(-a));
- *     ReLU expert: relu(x W1) W2; no biases; an expert is 3*d*f (resp. 2*d*f)
- *     parameters, matching the 176.16 M the paper states for Mixtral;
+ *     ReLU expert: relu(x W1) W2; GELU expert: gelu(x W1) W2 with
+ *     gelu(a) = a * Phi(a) = a/2 * (1 + erf(a / sqrt 2)); no biases; an expert
+ *     is 3*d*f (resp. 2*d*f) parameters, matching the 176.16 M the paper states
+ *     for Mixtral;
  *   - bf16 storage: every stored tensor is bf16; sums are carried in fp64 here;
  *     the activation H is rounded to bf16 before the second product.
  *
@@ -50,7 +59,8 @@
 #endif
 
 enum { ORC_F32 = 0, ORC_BF16 = 1 };
-enum { ORC_RELU = 0, ORC_SWIGLU = 1 };
+enum { ORC_RELU = 0, ORC_SWIGLU = 1, ORC_GELU = 2 };
+enum { ORC_GATE_SELECTED = 0, ORC_GATE_ALL = 1 };
 
 int mmoe_oracle_threads(void)
 {
@@ -110,7 +120,7 @@ static float canonical_dot(const void *x, size_t xoff, const void *w, size_t wof
 /*
  * topk_idx [T,k] int32, topk_w [T,k] double, logits [T,E] float (may be NULL).
  */
-void mmoe_oracle_route(int T, int d, int V, int E, int k, int dtype, const void *X,
+void mmoe_oracle_route(int T, int d, int V, int E, int k, int dtype, int gate, const void *X,
                        const int32_t *vid, const void *Wr, const float *br,
                        int32_t *topk_idx, double *topk_w, float *logits)
 {
@@ -145,6 +155,11 @@ void mmoe_oracle_route(int T, int d, int V, int E, int k, int dtype, const void 
             double ej = exp((double)lg[topk_idx[(size_t)t * k + j]] - m);
             topk_w[(size_t)t * k + j] = ej;
             z += ej;
+        }
+        if (gate == ORC_GATE_ALL) { /* the normaliser runs over every expert, selected or not */
+            z = 0.0;
+            for (int e = 0; e < E; ++e)
+                z += exp((double)lg[e] - m);
         }
         for (int j = 0; j < k; ++j)
             topk_w[(size_t)t * k + j] /= z;
@@ -213,6 +228,8 @@ static void ffn_row(int d, int f, int dtype, int act, const void *Xsrc, size_t x
         double h;
         if (act == ORC_SWIGLU)
             h = g[n] / (1.0 + exp(-g[n])) * u[n];
+        else if (act == ORC_GELU)
+            h = 0.5 * g[n] * (1.0 + erf(g[n] / sqrt(2.0)));
         else
             h = g[n] > 0.0 ? g[n] : 0.0;
         g[n] = dtype == ORC_BF16 ? round_to_bf16(h) : h;

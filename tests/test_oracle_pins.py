@@ -21,12 +21,12 @@ def as_f64(a, dtype):
     return (synth.bf16_bits_to_f32(a) if dtype == "bf16" else a).astype(np.float64)
 
 
-def run_brute(inp, cfg):
+def run_brute(inp, cfg, gate="selected"):
     dt = cfg.dtype
     f32 = lambda a: None if a is None else (synth.bf16_bits_to_f32(a) if dt == "bf16" else a)
     return bruteforce.layer(f32(inp["X"]), inp["vid"], f32(inp["Wr"]), inp["br"], inp["M"],
                             as_f64(inp["W1"], dt), as_f64(inp["W3"], dt), as_f64(inp["W2"], dt),
-                            cfg.top_k, cfg.act, bf16_h=(dt == "bf16"))
+                            cfg.top_k, cfg.act, bf16_h=(dt == "bf16"), gate=gate)
 
 
 TINY = [
@@ -51,6 +51,81 @@ def test_staged_oracle_equals_per_token_bruteforce(oracle, kw):
     toks = [0, cfg.T - 1, cfg.T // 2]
     Ys = oracle.layer_tokens(inp, cfg.top_k, cfg.dtype, cfg.act, toks)
     np.testing.assert_allclose(Ys, Y[toks], rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32", act="gelu", top_k=1, V=3, E=4),
+    dict(dtype="bf16", act="gelu", top_k=2, V=2, E=5, bias_alpha=0.4),
+    dict(dtype="f32", act="relu", top_k=4, V=3, E=6),
+    dict(dtype="bf16", act="swiglu", top_k=4, V=2, E=4),      # k = E
+])
+def test_gate_over_all_experts_and_gelu_equal_the_bruteforce(oracle, kw):
+    """The Switch-style gate (probability over all experts, not renormalised) and the GELU
+    expert against the independent per-token implementation."""
+    cfg = synth.tiny_config(seed=5, **kw)
+    inp = synth.make_inputs(cfg)
+    for gate in ("all", "selected"):
+        got = oracle.layer_forward(inp, cfg.top_k, cfg.dtype, cfg.act, gate=gate)
+        idx, w, Y = run_brute(inp, cfg, gate)
+        assert np.array_equal(got["topk_idx"], idx)
+        np.testing.assert_allclose(got["topk_w"], w, rtol=1e-14, atol=0)
+        np.testing.assert_allclose(got["Y"], Y, rtol=1e-11, atol=1e-13)
+
+
+def test_gate_over_all_experts_closed_forms(oracle):
+    """Gate mode "all": every selected expert keeps its entry of the softmax over ALL logits.
+    Pins: a library softmax; the coefficients do NOT sum to 1 unless every expert is selected;
+    renormalising them gives the other gate mode; two experts, top-1: 1 / (1 + e^(l_other - l_top))."""
+    cfg = synth.tiny_config(seed=6, T=40, E=6, V=3, top_k=2, d_model=64, bias_alpha=0.3)
+    inp = synth.make_inputs(cfg, weights=False)
+    idx, w, logits = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], 2, "f32", gate="all")
+    probs = torch.softmax(torch.from_numpy(logits).double(), dim=1).numpy()
+    np.testing.assert_allclose(w, np.take_along_axis(probs, idx, 1), rtol=1e-13)
+    assert np.all(w.sum(1) < 1.0 - 1e-3)                       # four experts were left out
+    idx_s, w_s, _ = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], 2, "f32", gate="selected")
+    assert np.array_equal(idx, idx_s)                          # the mode changes coefficients, never picks
+    np.testing.assert_allclose(w / w.sum(1, keepdims=True), w_s, rtol=1e-14)
+    # every expert selected: both modes coincide and sum to 1
+    _, w_all, _ = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], 6, "f32", gate="all")
+    _, w_sel, _ = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], 6, "f32", gate="selected")
+    np.testing.assert_allclose(w_all, w_sel, rtol=1e-14)
+    np.testing.assert_allclose(w_all.sum(1), 1.0, rtol=1e-14)
+    # two experts, top-1 (the Switch case): the logistic function of the logit gap
+    cfg2 = synth.tiny_config(seed=7, T=30, E=2, V=1, top_k=1, d_model=32)
+    inp2 = synth.make_inputs(cfg2, weights=False)
+    idx2, w2, lg2 = oracle.route(inp2["X"], inp2["vid"], inp2["Wr"], None, 1, "f32", gate="all")
+    top = np.take_along_axis(lg2, idx2, 1)[:, 0].astype(np.float64)
+    other = np.take_along_axis(lg2, 1 - idx2, 1)[:, 0].astype(np.float64)
+    np.testing.assert_allclose(w2[:, 0], 1.0 / (1.0 + np.exp(other - top)), rtol=1e-14)
+    assert np.all(w2 > 0.5) and np.all(w2 < 1.0)               # the top-1 weight is a probability, not 1
+
+
+def test_switch_style_layer_is_the_dense_definition(oracle):
+    """Identity table, one variant, top-1 with the probability as the coefficient and a GELU
+    expert: Y[t] = p[t, e*] * gelu(x W1[e*]) W2[e*], written here with library routines."""
+    cfg = synth.tiny_config(seed=8, T=12, d_model=16, d_ff=20, V=1, E=4, top_k=1, dtype="f32", act="gelu")
+    inp = synth.make_inputs(cfg)
+    got = oracle.layer_forward(inp, 1, "f32", "gelu", gate="all")
+    X = torch.from_numpy(inp["X"]).double()
+    logits = torch.from_numpy(got["logits"]).double()
+    p = torch.softmax(logits, 1)
+    Y = torch.zeros(cfg.T, cfg.d_model, dtype=torch.float64)
+    for e in range(cfg.E):
+        W1, W2 = torch.from_numpy(inp["W1"][e]).double(), torch.from_numpy(inp["W2"][e]).double()
+        ye = torch.nn.functional.gelu(X @ W1) @ W2              # the library's exact (erf) GELU
+        Y += (logits.argmax(1) == e).double()[:, None] * p[:, e:e + 1] * ye
+    np.testing.assert_allclose(got["Y"], Y.numpy(), rtol=1e-12, atol=1e-14)
+    # special values of the activation through d = f = 1: gelu(0) = 0, gelu(a) -> a, gelu(-a) -> 0,
+    # and gelu(a) - gelu(-a) = a exactly in exact arithmetic
+    one = np.ones((1, 1, 1), np.float32)
+    for a in (0.0, 0.5, 3.0, 12.0):
+        xs = np.array([[a], [-a]], np.float32)
+        tiny = dict(X=xs, vid=np.zeros(2, np.int32), Wr=one, br=None, M=np.zeros((1, 1), np.int32), S=1,
+                    W1=one, W3=None, W2=one)
+        y = oracle.layer_forward(tiny, 1, "f32", "gelu")["Y"][:, 0]
+        np.testing.assert_allclose(y[0] - y[1], a, rtol=1e-15, atol=1e-300)
+        np.testing.assert_allclose(y[0], a * 0.5 * math.erfc(-a / math.sqrt(2.0)), rtol=1e-14)
+    assert y[0] == 12.0 and abs(y[1]) < 1e-30
 
 
 def test_router_logits_bitexact_vs_exact_rational(oracle):
