@@ -130,7 +130,7 @@ def run_workload(cfg, inp, pool, steps, warmup):
     from paper_2505_06481_amd import mmoe
 
     S = int(inp["S"])
-    shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act)
+    shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act, gate=cfg.gate)
     X, Wr = to_dev(inp["X"]), to_dev(inp["Wr"])
     vid, M = torch.from_numpy(inp["vid"]).cuda(), torch.from_numpy(inp["M"]).cuda()
     br = None if inp["br"] is None else torch.from_numpy(inp["br"]).cuda()
@@ -241,7 +241,7 @@ def cpu_baseline(cfg, inp, n_tokens, res):
     n = n_tokens if n_tokens > 0 else 96 * threads
     n = min(n, cfg.T)
     t0 = time.perf_counter()
-    idx, w, _ = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], cfg.top_k, cfg.dtype)
+    idx, w, _ = oracle.route(inp["X"], inp["vid"], inp["Wr"], inp["br"], cfg.top_k, cfg.dtype, cfg.gate)
     slot, _, _, perm, _ = oracle.remap_group(inp["vid"], idx, inp["M"], int(inp["S"]))
     t_route = time.perf_counter() - t0
     toks = np.sort(np.random.default_rng(0).choice(cfg.T, n, replace=False))
@@ -285,7 +285,7 @@ def main():
     cfg = synth.CONFIGS[a.workload]
     inp = synth.make_inputs(cfg)
     S = int(inp["S"])
-    shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act)
+    shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act, gate=cfg.gate)
     W1, W3, W2 = (to_dev(inp[k]) for k in ("W1", "W3", "W2"))
     pool = mmoe.pack_weights(shape, W1, W3, W2)   # one-time repacking at pool load, untimed
     if a.zero_pool:
@@ -392,7 +392,7 @@ def main():
         cfg2 = cfg.replace(seed=cfg.seed + 1)
         inp2 = synth.make_inputs(cfg2)
         S2 = int(inp2["S"])
-        shape2 = mmoe.make_shape(cfg2.T, cfg2.d_model, cfg2.d_ff, cfg2.V, cfg2.E, S2, cfg2.top_k, cfg2.dtype, cfg2.act)
+        shape2 = mmoe.make_shape(cfg2.T, cfg2.d_model, cfg2.d_ff, cfg2.V, cfg2.E, S2, cfg2.top_k, cfg2.dtype, cfg2.act, gate=cfg2.gate)
         W1, W3, W2 = (to_dev(inp2[k]) for k in ("W1", "W3", "W2"))
         pool2 = mmoe.pack_weights(shape2, W1, W3, W2)
         torch.cuda.synchronize()

@@ -39,7 +39,7 @@
  * Limits
  *   d_model and d_ff multiples of 256; E <= 256; top_k <= min(E, 8); S <= 1024;
  *   P*max(d,f) < 2^35, and < 2^31 for bf16 batches large enough for the matrix-core expert
- *   kernels (P > 16*S, or 32*S when d*f <= 4 Mi): otherwise MMOE_ERR_LIMIT.  SWIGLU needs W3, RELU needs W3 == NULL.
+ *   kernels (P > 16*S, or 32*S when d*f <= 4 Mi): otherwise MMOE_ERR_LIMIT.  SWIGLU needs W3, RELU and GELU need W3 == NULL.
  */
 #ifndef MMOE_H
 #define MMOE_H
@@ -52,15 +52,27 @@ extern "C" {
 #endif
 
 typedef enum { MMOE_F32 = 0, MMOE_BF16 = 1 } mmoe_dtype;
-typedef enum { MMOE_RELU = 0, MMOE_SWIGLU = 1 } mmoe_act;
+typedef enum { MMOE_RELU = 0, MMOE_SWIGLU = 1, MMOE_GELU = 2 } mmoe_act;
+/*
+ * How the gate's coefficients are formed (section 3.2: "the gate network generates weighted
+ * averaging coefficients for each expert, and ... the top experts are selected"; the paper gives
+ * no formula, and its two model families differ):
+ *   MMOE_GATE_SELECTED  softmax over the k selected logits; the coefficients of a token sum to 1
+ *                       (k = 1 gives exactly 1).  The Mixtral-style top-2 gate.
+ *   MMOE_GATE_ALL       softmax over all E logits; every selected expert keeps its own probability,
+ *                       nothing is renormalised, so the coefficients sum to less than 1 unless
+ *                       k = E.  The Switch-style top-1 gate (section 4.3's model family).
+ * The selection itself (k largest logits, ties to the lower index) is the same in both.
+ */
+typedef enum { MMOE_GATE_SELECTED = 0, MMOE_GATE_ALL = 1 } mmoe_gate;
 
 typedef enum {
     MMOE_OK = 0,
     MMOE_ERR_NULL = -1,      /* a required pointer is NULL                               */
     MMOE_ERR_DIM = -2,       /* a dimension is not positive                              */
     MMOE_ERR_TOPK = -3,      /* top_k > E or top_k > 8                                   */
-    MMOE_ERR_DTYPE = -4,     /* unknown dtype or activation code                         */
-    MMOE_ERR_W3 = -5,        /* W3 missing for SWIGLU, or given for RELU                 */
+    MMOE_ERR_DTYPE = -4,     /* unknown dtype, activation or gate code                   */
+    MMOE_ERR_W3 = -5,        /* W3 missing for SWIGLU, or given for RELU / GELU          */
     MMOE_ERR_WORKSPACE = -6, /* ws is NULL or ws_bytes too small                         */
     MMOE_ERR_ALIGN = -7,     /* a tensor pointer is not 16-byte (ws: 256-byte) aligned   */
     MMOE_ERR_MULTIPLE = -8,  /* d_model or d_ff is not a multiple of 256                 */
@@ -79,6 +91,7 @@ typedef struct {
     int32_t top_k;   /* experts selected per token               */
     int32_t dtype;   /* mmoe_dtype                               */
     int32_t act;     /* mmoe_act                                 */
+    int32_t gate;    /* mmoe_gate                                */
     int32_t tile_rows; /* tuning, normally 0: token rows per tile of the matrix-core expert kernels.
                           0 chooses by shape: 128 rows (two workgroups per compute unit) when tiles are
                           short-lived (d_model <= 1024, or fewer than 64 rows per slot on average), 256
@@ -105,7 +118,7 @@ const char *mmoe_strerror(int status);
  *         with m = k/64, h = (k%64)/32, kk = (k%32)/8, ks = 4*m + kk:
  *         the 64 pieces of 16 bytes that follow each other are exactly the 32-row x 16-k
  *         operand of v_mfma_f32_32x32x16_bf16 as its 64 lanes hold it.
- * W3/W3p are NULL for RELU.  Outputs must not overlap inputs.
+ * W3/W3p are NULL for RELU and GELU.  Outputs must not overlap inputs.
  */
 int mmoe_pack_weights(const mmoe_shape *shape, const void *W1, const void *W3, const void *W2,
                       void *W1p, void *W3p, void *W2p, void *stream);
@@ -114,7 +127,8 @@ int mmoe_pack_weights(const mmoe_shape *shape, const void *W1, const void *W3, c
  * Step R -- gate of the requested variant (Algorithm 2, "gate(act)"; section 3.2).
  *   logit[t,e] = <X[t,:], Wr[vid[t],e,:]> (+ br[vid[t],e])
  *   the k largest logits are selected, ties to the lower expert index, listed in
- *   selection (descending) order; w[t,j] = softmax over the k selected logits.
+ *   selection (descending) order; w[t,j] = softmax over the k selected logits
+ *   (MMOE_GATE_SELECTED) or entry j's probability in the softmax over all E logits (MMOE_GATE_ALL).
  * The logit is an fp32 sum in a fixed order, so that the selected indices are
  * reproducible bit for bit: element i belongs to lane (i div 4) mod 64; a lane
  * accumulates its elements in ascending i with one fused multiply-add each,
@@ -149,6 +163,7 @@ int mmoe_remap_permute(const mmoe_shape *shape, const void *X, const int32_t *vi
  * For every slot s and row r in [offsets[s], offsets[s+1]):
  *   SWIGLU: Yg[r,:] = (silu(Xg[r,:] W1[s]) * (Xg[r,:] W3[s])) W2[s],  silu(a) = a/(1+exp(-a))
  *   RELU:   Yg[r,:] = relu(Xg[r,:] W1[s]) W2[s]
+ *   GELU:   Yg[r,:] = gelu(Xg[r,:] W1[s]) W2[s],  gelu(a) = a/2 (1 + erf(a / sqrt 2))
  * Products accumulate in fp32; the hidden activation is stored in `dtype`
  * (rounded to nearest even for bf16) between the two products.
  *   Xg [P,d] dtype; offsets [S+1] int32 (device); W1p, W3p, W2p: PACKED pool

@@ -31,7 +31,7 @@
 
 namespace mmoe {
 
-enum { kModeReluH = 0, kModeSwigluH = 1, kModePlainF32 = 2 };
+enum { kModeReluH = 0, kModeSwigluH = 1, kModePlainF32 = 2, kModeGeluH = 3 };
 
 constexpr int kSkThreads = 256;
 constexpr int kSkWaves = 4;
@@ -49,6 +49,7 @@ template <> struct Mma<float> {  // fp32, 16x16x4: one 16-byte piece = 4 element
 };
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+__device__ __forceinline__ float gelu(float a) { return 0.5f * a * (1.0f + erff(a * 0.70710678118654752440f)); }
 
 constexpr int kSelfMaxP = 1024;  // most pairs for which the expert kernels group by themselves
 
@@ -220,6 +221,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
                 for (int i = 0; i < 4; ++i) {
                     if (MODE == kModeSwigluH) o[i] = silu_mul(v[0][i], v[NW - 1][i]);
                     else if (MODE == kModeReluH) o[i] = fmaxf(v[0][i], 0.0f);
+                    else if (MODE == kModeGeluH) o[i] = gelu(v[0][i]);
                     else o[i] = v[0][i];
                 }
                 const size_t at = (size_t)rs.out_row(row) * N + n0 + 4 * (l >> 4);
@@ -352,6 +354,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
                         v[w] = (red[0][w][l][e] + red[1][w][l][e]) + (red[2][w][l][e] + red[3][w][l][e]);
                     if (MODE == kModeSwigluH) o[i] = silu_mul(v[0], v[NW - 1]);
                     else if (MODE == kModeReluH) o[i] = fmaxf(v[0], 0.0f);
+                    else if (MODE == kModeGeluH) o[i] = gelu(v[0]);
                     else o[i] = v[0];
                 }
                 const size_t at = (size_t)rs.out_row(row) * N + nb * 32 + 8 * q + 4 * (l >> 5);
@@ -381,6 +384,9 @@ static int run_skinny_bf16(const mmoe_shape& s, const void* rows, const int32_t*
     if (s.act == MMOE_SWIGLU)
         hipLaunchKernelGGL((skinny_frag_kernel<2, 1, kModeSwigluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
                            s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f);
+    else if (s.act == MMOE_GELU)
+        hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeGeluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
+                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f);
     else
         hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeReluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
                            s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f);
@@ -403,6 +409,9 @@ static int run_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm
     if (s.act == MMOE_SWIGLU)
         hipLaunchKernelGGL((skinny_kernel<T, 2, 1, kModeSwigluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
                            offsets, slot_of_pair, P, (const T*)W1p, (const T*)W3p, H, d, f);
+    else if (s.act == MMOE_GELU)
+        hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeGeluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
+                           offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f);
     else
         hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
                            offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f);

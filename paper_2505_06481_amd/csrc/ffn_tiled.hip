@@ -33,7 +33,7 @@
 
 namespace mmoe {
 
-enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2 };
+enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2, kTModeGeluH = 3 };
 
 constexpr int kBN = 256;  // weight rows per tile
 constexpr int kBK = 64;
@@ -366,6 +366,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
             for (int e = 0; e < 16; ++e) {
                 if (MODE == kTModeSwigluH) o[e] = silu_mul_t(acc[j][0][e], acc[j][1][e]);
                 else if (MODE == kTModeReluH) o[e] = fmaxf(acc[j][c][e], 0.0f);
+                else if (MODE == kTModeGeluH) o[e] = 0.5f * acc[j][c][e] * (1.0f + erff(acc[j][c][e] * 0.70710678118654752440f));
                 else o[e] = acc[j][c][e];
             }
             emit(j, c, o);
@@ -413,6 +414,10 @@ static void launch_tiled_products(const mmoe_shape& s, const TileLists& L, const
         hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH, BM>), dim3(L.cap[0] * kXcds), block, 0, st,
                            (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
                            (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, nt_up);
+    else if (s.act == MMOE_GELU)
+        hipLaunchKernelGGL((tiled_kernel<kTModeGeluH, BM>), dim3(L.cap[0] * kXcds), block, 0, st,
+                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
+                           (const uint16_t*)W1p, nul, H, d, f, nt_up);
     else
         hipLaunchKernelGGL((tiled_kernel<kTModeReluH, BM>), dim3(L.cap[0] * kXcds), block, 0, st,
                            (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],

@@ -12,7 +12,8 @@ int check_shape(const mmoe_shape* s)
     if (s->T <= 0 || s->d_model <= 0 || s->d_ff <= 0 || s->V <= 0 || s->E <= 0 || s->S <= 0 || s->top_k <= 0)
         return MMOE_ERR_DIM;
     if (s->dtype != MMOE_F32 && s->dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
-    if (s->act != MMOE_RELU && s->act != MMOE_SWIGLU) return MMOE_ERR_DTYPE;
+    if (s->act != MMOE_RELU && s->act != MMOE_SWIGLU && s->act != MMOE_GELU) return MMOE_ERR_DTYPE;
+    if (s->gate != MMOE_GATE_SELECTED && s->gate != MMOE_GATE_ALL) return MMOE_ERR_DTYPE;
     if (s->tile_rows != 0 && s->tile_rows != 128 && s->tile_rows != 256) return MMOE_ERR_DIM;
     if (s->top_k > s->E || s->top_k > kMaxTopK) return MMOE_ERR_TOPK;
     if (s->d_model % 256 != 0 || s->d_ff % 256 != 0) return MMOE_ERR_MULTIPLE;
@@ -84,8 +85,8 @@ const char* mmoe_strerror(int status)
         case MMOE_ERR_NULL: return "a required pointer is NULL";
         case MMOE_ERR_DIM: return "a dimension is not positive";
         case MMOE_ERR_TOPK: return "top_k exceeds E or the supported maximum of 8";
-        case MMOE_ERR_DTYPE: return "unknown dtype or activation";
-        case MMOE_ERR_W3: return "W3 must be given for SWIGLU and must be NULL for RELU";
+        case MMOE_ERR_DTYPE: return "unknown dtype, activation or gate mode";
+        case MMOE_ERR_W3: return "W3 must be given for SWIGLU and must be NULL for RELU and GELU";
         case MMOE_ERR_WORKSPACE: return "workspace missing or smaller than mmoe_workspace_bytes()";
         case MMOE_ERR_ALIGN: return "a pointer is not sufficiently aligned (16 bytes; workspace 256)";
         case MMOE_ERR_MULTIPLE: return "d_model and d_ff must be multiples of 256";

@@ -12,6 +12,9 @@
 //
 // Logits are parked in LDS, then the k winners are found by wavefront arg-max
 // reductions: lane l looks after experts l, l+64, ...; ties go to the lower index.
+// Coefficients: softmax over the selected logits, or (gate over all experts) each selected
+// expert's entry of the softmax over all E logits, whose normaliser is one more wavefront
+// reduction over the parked logits.
 #include "mmoe_internal.h"
 
 namespace mmoe {
@@ -45,7 +48,8 @@ template <> struct Vec4<uint16_t> {
 // groups the pairs itself.
 __device__ __forceinline__ void select_topk(const float* __restrict__ lds_logit, int lane, int E, int k, int t,
                                             int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-                                            const int32_t* __restrict__ map_row, int32_t* __restrict__ slot, int S)
+                                            const int32_t* __restrict__ map_row, int32_t* __restrict__ slot, int S,
+                                            int gate)
 {
     constexpr int kPerLane = kMaxE / kWave;
     float mine[kPerLane];
@@ -83,6 +87,16 @@ __device__ __forceinline__ void select_topk(const float* __restrict__ lds_logit,
             if ((be & (kWave - 1)) == lane) taken |= 1u << (be / kWave);
         }
     }
+    // gate over all experts: the normaliser is the sum of exp(logit - largest logit) over every expert
+    // (sel[0] is the largest); fp32, lane-local in ascending expert index, then an xor butterfly
+    float all = 0.0f;
+    if (gate == MMOE_GATE_ALL) {
+#pragma unroll
+        for (int q = 0; q < kPerLane; ++q)
+            if (lane + q * kWave < E) all += expf(mine[q] - sel[0]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) all += __shfl_xor(all, off, kWave);
+    }
     if (lane == 0) {
         float z[kMaxTopK];
         float tot = 0.0f;
@@ -92,6 +106,7 @@ __device__ __forceinline__ void select_topk(const float* __restrict__ lds_logit,
                 z[j] = expf(sel[j] - sel[0]);
                 tot += z[j];
             }
+        if (gate == MMOE_GATE_ALL) tot = all;
 #pragma unroll
         for (int j = 0; j < kMaxTopK; ++j)
             if (j < k) {
@@ -111,7 +126,7 @@ template <typename T>
 __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     const T* __restrict__ X, const int32_t* __restrict__ vid, const T* __restrict__ Wr,
     const float* __restrict__ br, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d,
-    int V, int E, int k, const int32_t* __restrict__ M, int32_t* __restrict__ slot, int S)
+    int V, int E, int k, const int32_t* __restrict__ M, int32_t* __restrict__ slot, int S, int gate)
 {
     __shared__ float lds_logit[kMaxE];
     const int lane = threadIdx.x & (kWave - 1);
@@ -154,7 +169,7 @@ __global__ __launch_bounds__(kRouteWaves* kWave) void route_kernel(
     __syncthreads();
     if (wave != 0) return;
 
-    select_topk(lds_logit, lane, E, k, t, topk_idx, topk_w, M ? M + (size_t)v * E : nullptr, slot, S);
+    select_topk(lds_logit, lane, E, k, t, topk_idx, topk_w, M ? M + (size_t)v * E : nullptr, slot, S, gate);
 }
 
 // Four consecutive elements as loaded (bf16 stays packed until it is used, which halves the
@@ -187,7 +202,7 @@ template <typename T, int NC>
 __global__ __launch_bounds__(kRouteTokWaves* kWave) void route_token_kernel(
     const T* __restrict__ X, const int32_t* __restrict__ vid, const T* __restrict__ Wr,
     const float* __restrict__ br, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int Tn, int d,
-    int V, int E, int k, const int32_t* __restrict__ M, int32_t* __restrict__ slot, int S)
+    int V, int E, int k, const int32_t* __restrict__ M, int32_t* __restrict__ slot, int S, int gate)
 {
     __shared__ float lds_logit[kRouteTokWaves][kMaxE];
     const int lane = threadIdx.x & (kWave - 1);
@@ -241,7 +256,7 @@ __global__ __launch_bounds__(kRouteTokWaves* kWave) void route_token_kernel(
     // program order, the fence keeps the compiler from moving them
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    select_topk(mylogit, lane, E, k, t, topk_idx, topk_w, M ? M + (size_t)v * E : nullptr, slot, S);
+    select_topk(mylogit, lane, E, k, t, topk_idx, topk_w, M ? M + (size_t)v * E : nullptr, slot, S, gate);
 }
 
 int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const void* Wr, const float* br,
@@ -257,10 +272,10 @@ int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const v
     case NC:                                                                                                        \
         if (s.dtype == MMOE_BF16)                                                                                   \
             hipLaunchKernelGGL((route_token_kernel<uint16_t, NC>), grid, block, 0, st, (const uint16_t*)X, vid,     \
-                               (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S);       \
+                               (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S, s.gate);       \
         else                                                                                                        \
             hipLaunchKernelGGL((route_token_kernel<float, NC>), grid, block, 0, st, (const float*)X, vid,           \
-                               (const float*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S);          \
+                               (const float*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S, s.gate);          \
         break
         switch (nc) {
             MMOE_ROUTE_TOK(1);
@@ -278,10 +293,10 @@ int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const v
     dim3 grid(s.T), block(kRouteWaves * kWave);
     if (s.dtype == MMOE_BF16)
         hipLaunchKernelGGL(route_kernel<uint16_t>, grid, block, 0, st, (const uint16_t*)X, vid,
-                           (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S);
+                           (const uint16_t*)Wr, br, topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S, s.gate);
     else
         hipLaunchKernelGGL(route_kernel<float>, grid, block, 0, st, (const float*)X, vid, (const float*)Wr, br,
-                           topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S);
+                           topk_idx, topk_w, s.T, s.d_model, s.V, s.E, s.top_k, M, slot, s.S, s.gate);
     return launch_status();
 }
 

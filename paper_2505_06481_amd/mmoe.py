@@ -18,9 +18,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmmoe.so")
 
 F32, BF16 = 0, 1
-RELU, SWIGLU = 0, 1
+RELU, SWIGLU, GELU = 0, 1, 2
+GATE_SELECTED, GATE_ALL = 0, 1
 _DTYPES = {"f32": F32, "bf16": BF16}
-_ACTS = {"relu": RELU, "swiglu": SWIGLU}
+_ACTS = {"relu": RELU, "swiglu": SWIGLU, "gelu": GELU}
+_GATES = {"selected": GATE_SELECTED, "all": GATE_ALL}
 _TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
 
 EXPORTS = [
@@ -38,14 +40,17 @@ class MmoeError(RuntimeError):
 
 class Shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("T", "d_model", "d_ff", "V", "E", "S", "top_k", "dtype", "act", "tile_rows")]
+                ("T", "d_model", "d_ff", "V", "E", "S", "top_k", "dtype", "act", "gate", "tile_rows")]
 
 
-def make_shape(T, d_model, d_ff, V, E, S, top_k, dtype, act, tile_rows=0) -> Shape:
-    """``tile_rows``: tuning field of the matrix-core expert kernels, 0 = chosen by shape."""
+def make_shape(T, d_model, d_ff, V, E, S, top_k, dtype, act, tile_rows=0, gate="selected") -> Shape:
+    """``gate``: "selected" (softmax over the selected logits) or "all" (probabilities over all
+    experts, not renormalised).  ``tile_rows``: tuning field of the matrix-core expert kernels,
+    0 = chosen by shape."""
     dt = _DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
     ac = _ACTS[act] if isinstance(act, str) else int(act)
-    return Shape(T, d_model, d_ff, V, E, S, top_k, dt, ac, tile_rows)
+    ga = _GATES[gate] if isinstance(gate, str) else int(gate)
+    return Shape(T, d_model, d_ff, V, E, S, top_k, dt, ac, ga, tile_rows)
 
 
 _lib = None

@@ -99,7 +99,7 @@ class Config:
     E: int
     top_k: int
     dtype: str  # "f32" | "bf16"
-    act: str  # "relu" | "swiglu"
+    act: str  # "relu" | "swiglu" | "gelu"
     vid_mode: str = "uniform"  # "uniform" | "interleave" | "zipf"
     vid_zipf_s: float = 1.2
     # br[v][e] = -alpha * ln(e + 1); 0 -> no bias tensor.  alpha = 1 is a Zipf(1) prior over the
@@ -109,6 +109,7 @@ class Config:
     share_prob: float = 0.5
     w_sigma: float = 0.02
     seed: int = 0
+    gate: str = "selected"  # "selected": softmax over the picks; "all": probabilities over all experts
 
     @property
     def P(self) -> int:
@@ -131,6 +132,9 @@ CONFIGS: Dict[str, Config] = {
                vid_mode="interleave"),
         Config("mixtral_skew_bf16_v4_t16384", 16384, 4096, 14336, 4, 8, 2, "bf16", "swiglu",
                vid_mode="zipf", bias_alpha=2.5),
+        # beyond the five: the Switch family's own gate (top-1 probability over all experts, not
+        # renormalised) in the three-variant scenario of the paper's scalability experiment (section 4.3)
+        Config("switch8_bf16_v3_t4096_gate_all", 4096, 768, 3072, 3, 8, 1, "bf16", "relu", gate="all"),
     ]
 }
 

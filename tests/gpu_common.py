@@ -34,7 +34,7 @@ class DeviceCase:
         i = self.inp
         self.S = int(i["S"])
         self.shape = mmoe.make_shape(cfg.T, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, self.S, cfg.top_k, cfg.dtype, cfg.act,
-                                     tile_rows=tile_rows)
+                                     tile_rows=tile_rows, gate=cfg.gate)
         dt = cfg.dtype
         self.X, self.Wr = to_dev(i["X"], dt), to_dev(i["Wr"], dt)
         self.vid = torch.from_numpy(i["vid"]).cuda()

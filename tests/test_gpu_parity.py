@@ -37,7 +37,7 @@ def staged_vs_oracle(mm, gc, oracle, cfg, inp=None, tile_rows=0):
           f"{cfg.dtype} {cfg.act} seed={cfg.seed}", flush=True)
     case = gc.DeviceCase(cfg, inp, tile_rows=tile_rows)
     inp, sh, dt = case.inp, case.shape, cfg.dtype
-    ref = oracle.layer_forward(inp, cfg.top_k, dt, cfg.act)
+    ref = oracle.layer_forward(inp, cfg.top_k, dt, cfg.act, gate=cfg.gate)
 
     idx, w = mm.route(sh, case.X, case.vid, case.Wr, case.br)
     torch.cuda.synchronize()
@@ -99,6 +99,31 @@ def test_both_tile_heights(mm, gc, oracle, cfg, rows):
     """The matrix-core kernels at a forced tile height (by shape these small batches would only
     ever get the 128-row tiles): every stage against the oracle, ragged last tiles of 1..8 sub-tiles."""
     staged_vs_oracle(mm, gc, oracle, cfg, tile_rows=rows)
+
+
+GATES_AND_ACTS = [
+    # Switch-style gate (probability over all experts, not renormalised), top-1, ReLU and GELU experts,
+    # three variants; streaming kernels and matrix-core kernels, fp32 and bf16
+    synth.Config("g_switch_f32_gelu", 60, 256, 512, 3, 8, 1, "f32", "gelu", seed=41, gate="all"),
+    synth.Config("g_switch_bf16_relu_tiled", 1200, 256, 512, 3, 8, 1, "bf16", "relu", seed=42, gate="all"),
+    synth.Config("g_switch_bf16_gelu_tiled", 1000, 512, 768, 3, 8, 1, "bf16", "gelu", seed=43, gate="all"),
+    synth.Config("g_switch_bf16_gelu_stream", 90, 512, 256, 3, 8, 1, "bf16", "gelu", seed=44, gate="all"),
+    # k = 2 and 4 with either gate, up to 64 experts per variant, gated and plain experts
+    synth.Config("g_all_k2_e64", 500, 256, 256, 2, 64, 2, "bf16", "swiglu", seed=45, gate="all"),
+    synth.Config("g_all_k4_e64", 300, 256, 256, 3, 64, 4, "bf16", "gelu", seed=46, gate="all", bias_alpha=0.5),
+    synth.Config("g_sel_k4_e16", 2100, 256, 256, 3, 16, 4, "bf16", "gelu", seed=47),
+    synth.Config("g_all_k4_f32", 2060, 512, 256, 3, 16, 4, "f32", "swiglu", seed=48, gate="all"),
+    synth.Config("g_all_k_equals_e", 70, 256, 256, 2, 4, 4, "f32", "relu", seed=49, gate="all"),   # sums to 1 again
+]
+
+
+@pytest.mark.parametrize("cfg", GATES_AND_ACTS, ids=lambda c: c.name)
+def test_gate_modes_and_activations(mm, gc, oracle, cfg):
+    """Section 3.2's coefficients "for each expert" read the Switch way (section 4.3's family), and the
+    GELU expert: every stage against the oracle, both router kernels, both expert-stage kernels."""
+    case, ref = staged_vs_oracle(mm, gc, oracle, cfg)
+    if cfg.gate == "all" and cfg.top_k < cfg.E:
+        assert (ref["topk_w"].sum(1) < 1.0).all()        # not renormalised
 
 
 def test_edge_cases(mm, gc, oracle):

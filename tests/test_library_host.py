@@ -54,6 +54,8 @@ def test_bad_arguments_become_error_codes(mm):
     assert route(mm.make_shape(4, 256, 256, 1, 16, 2, 9, "f32", "relu")) == -3           # top_k > 8
     assert route(mm.make_shape(4, 256, 256, 1, 2, 2, 1, 7, "relu")) == -4                # dtype
     assert route(mm.make_shape(4, 256, 256, 1, 2, 2, 1, "f32", 5)) == -4                 # activation
+    assert route(mm.make_shape(4, 256, 256, 1, 2, 2, 1, "f32", "gelu", gate=2)) == -4     # gate mode
+    assert route(mm.make_shape(4, 256, 256, 1, 2, 2, 1, "f32", "gelu", gate="all"), X=none) == -1
     assert route(mm.make_shape(4, 200, 256, 1, 2, 2, 1, "f32", "relu")) == -8            # multiple of 256
     assert route(mm.make_shape(4, 256, 256, 1, 300, 2, 1, "f32", "relu")) == -9          # E limit
     assert route(mm.make_shape(4, 256, 256, 1, 2, 5000, 1, "f32", "relu")) == -9         # S limit
@@ -66,6 +68,8 @@ def test_bad_arguments_become_error_codes(mm):
     gated = mm.make_shape(4, 256, 256, 1, 2, 2, 1, "bf16", "swiglu")
     assert L.mmoe_expert_ffn(ctypes.byref(gated), p, p, p, none, p, p, p, 1 << 30, none) == -5
     assert L.mmoe_expert_ffn(ctypes.byref(ok), p, p, p, p, p, p, p, 1 << 30, none) == -5
+    gelu = mm.make_shape(4, 256, 256, 1, 2, 2, 1, "bf16", "gelu")
+    assert L.mmoe_expert_ffn(ctypes.byref(gelu), p, p, p, p, p, p, p, 1 << 30, none) == -5   # GELU takes no W3
     assert L.mmoe_expert_ffn(ctypes.byref(ok), p, p, p, none, p, p, p, 16, none) == -6
     assert L.mmoe_expert_ffn(ctypes.byref(ok), p, p, p, none, p, p, none, 1 << 30, none) == -6
     assert L.mmoe_layer_forward(ctypes.byref(ok), p, p, p, none, p, p, none, p, p, ctypes.c_void_p(4352), 8,

@@ -168,7 +168,7 @@ def test_checker_flags_a_short_window():
 def test_every_written_out_wait_of_the_tiled_kernel_is_covered():
     text = device_assembly()
     fns = functions(text, "_ZN4mmoe12tiled_kernel")
-    assert len(fns) == 6, [f.name for f in fns]          # 3 products x 2 tile heights
+    assert len(fns) == 8, [f.name for f in fns]          # 4 products (three activations, down) x 2 tile heights
     for fn in fns:
         bm = int(re.search(r"ILi\d+ELi(\d+)EE", fn.name).group(1))
         knp = bm * 8 // 256                               # copies per wavefront and step
