@@ -284,3 +284,42 @@ void mmoe_oracle_combine(int T, int d, int k, const double *Yg, const int32_t *i
         }
     }
 }
+
+/* ---- Algorithm 1 (initial expert loader): degree of similarity of one expert location ------- */
+
+/*
+ * The paper flattens an expert block into one vector and takes the L2 distance between the
+ * experts that two models hold at the same (layer, expert) location; with more than two models the
+ * degree of similarity of the location is the sum over all model-to-model combinations
+ * (section 3.1).  Here: V models, the location's flattened expert of model v at ptrs[v]
+ * (n stored elements); returns  sum_{i<j} sqrt( sum_t (a_i[t] - a_j[t])^2 )  in double.
+ * The listing sums over ordered pairs, which doubles every location's value and ranks them
+ * the same.  Fixed partition into runs of 2^20 elements, partial sums added in ascending order:
+ * the result does not depend on the number of threads.
+ */
+double mmoe_oracle_location_distance(int V, size_t n, int dtype, const void *const *ptrs)
+{
+    const size_t run = (size_t)1 << 20;
+    const size_t nrun = (n + run - 1) / run;
+    double total = 0.0;
+    for (int i = 0; i < V; ++i)
+        for (int j = i + 1; j < V; ++j) {
+            double *part = (double *)malloc(sizeof(double) * (nrun ? nrun : 1));
+#pragma omp parallel for schedule(static)
+            for (size_t r = 0; r < nrun; ++r) {
+                size_t lo = r * run, hi = lo + run < n ? lo + run : n;
+                double acc = 0.0;
+                for (size_t t = lo; t < hi; ++t) {
+                    double df = (double)load_elem(ptrs[i], dtype, t) - (double)load_elem(ptrs[j], dtype, t);
+                    acc += df * df;
+                }
+                part[r] = acc;
+            }
+            double sq = 0.0;
+            for (size_t r = 0; r < nrun; ++r)
+                sq += part[r];
+            free(part);
+            total += sqrt(sq);
+        }
+    return total;
+}

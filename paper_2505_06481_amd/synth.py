@@ -214,3 +214,73 @@ def tiny_config(name="tiny", T=13, d_model=32, d_ff=48, V=2, E=4, top_k=2, dtype
                 act="swiglu", **kw) -> Config:
     """A small configuration for brute-force checks."""
     return Config(name, T, d_model, d_ff, V, E, top_k, dtype, act, **kw)
+
+
+# ---- variants of one model for the expert-map builder (Algorithm 1) ------------------------------
+_ST_BASE, _ST_DELTA, _ST_GAIN = 5000, 6000, 7000
+
+
+@dataclasses.dataclass(frozen=True)
+class TableConfig:
+    """Shapes of the models handed to the initial expert loader: V variants of one MoE model with
+    L layers of E experts; an expert block is `mats` matrices of d_model x d_ff elements."""
+    name: str
+    V: int
+    L: int
+    E: int
+    d_model: int
+    d_ff: int
+    act: str            # "relu" | "gelu": 2 matrices; "swiglu": 3
+    dtype: str
+    capacity: int       # expert locations that are consolidated
+    w_sigma: float = 0.02
+    ft_sigma: float = 3e-4   # fine-tuning drift per element: distances of a few units at Mixtral size
+    seed: int = 0
+
+    @property
+    def mats(self) -> int:
+        return 3 if self.act == "swiglu" else 2
+
+    @property
+    def n_params(self) -> int:
+        return self.mats * self.d_model * self.d_ff
+
+    def replace(self, **kw) -> "TableConfig":
+        return dataclasses.replace(self, **kw)
+
+
+TABLE_CONFIGS: Dict[str, TableConfig] = {
+    c.name: c
+    for c in [
+        # the paper's scalability scenario at full size: Switch-Base-8, 12 MoE layers, 4 variants
+        TableConfig("switch8_table_v4_l12", 4, 12, 8, 768, 3072, "relu", "bf16", capacity=48),
+        # Mixtral-8x7B-shaped experts (176.16 M parameters each), two variants, four layers
+        TableConfig("mixtral_table_v2_l4", 2, 4, 8, 4096, 14336, "swiglu", "bf16", capacity=16),
+    ]
+}
+
+
+def make_variants(cfg: TableConfig):
+    """variants[v][m]: matrix m of model v, shape [L, E, d_model*d_ff] (flattened), storage dtype.
+
+    Stand-in for fine-tuned checkpoints: a base model N(0, w_sigma^2) plus, for every variant, a
+    drift N(0, (ft_sigma * gain[l, e])^2) per element.  The gain grows with depth by about a third
+    (the paper's distance map shows same-position distances of 3.6 to 4.9, larger in deeper layers)
+    with a per-location jitter, so that the locations' distances are distinct at the percent level.
+    """
+    n = cfg.d_model * cfg.d_ff
+    jit = uniform(cfg.seed, _ST_GAIN, cfg.L * cfg.E).reshape(cfg.L, cfg.E)
+    depth = np.arange(cfg.L)[:, None] / max(cfg.L - 1, 1)
+    gain = 1.0 + 0.36 * depth + 0.1 * jit
+    np_dt = np.float32 if cfg.dtype == "f32" else np.uint16
+    out = [[np.empty((cfg.L, cfg.E, n), np_dt) for _ in range(cfg.mats)] for _ in range(cfg.V)]
+    for l in range(cfg.L):
+        for e in range(cfg.E):
+            for m in range(cfg.mats):
+                loc = (l * cfg.E + e) * cfg.mats + m
+                base = normal(cfg.seed, _ST_BASE + loc, (n,), cfg.w_sigma, "f32")
+                for v in range(cfg.V):
+                    drift = normal(cfg.seed, _ST_DELTA + loc * 64 + v, (n,), cfg.ft_sigma * float(gain[l, e]), "f32")
+                    w = base + drift
+                    out[v][m][l, e] = w if cfg.dtype == "f32" else f32_to_bf16_bits(w)
+    return out
