@@ -74,6 +74,9 @@ def parse():
                     help="after the main workload (Mixtral-shaped pools only): the layer at 1, 2, 4, ... 64 tokens on "
                          "the same pool, with the weight bytes of the slots each batch touches and the fraction of "
                          "HBM peak over the whole layer")
+    ap.add_argument("--loader", default=None, metavar="TABLE_WORKLOAD",
+                    help="instead of the layer: time the expert-map builder (Algorithm 1) on one of "
+                         "synth.TABLE_CONFIGS; one step = distances of every expert location + ranking + tables")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference point for HBM byte counters)")
     return ap.parse_args()
@@ -270,11 +273,94 @@ def cpu_baseline(cfg, inp, n_tokens, res):
     return base, parity
 
 
+def bench_loader(a):
+    """The initial expert loader's table (Algorithm 1): every variant's experts resident in HBM, one step
+    = distances of all locations, ranking, owners and per-layer tables.  HBM-bound: every stored element
+    is read once."""
+    import numpy as np
+    import torch
+
+    from paper_2505_06481_amd import mmoe, synth
+
+    mmoe.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = synth.TABLE_CONFIGS[a.loader]
+    t0 = time.perf_counter()
+    variants = synth.make_variants(cfg)
+    t_gen = time.perf_counter() - t0
+    sh = mmoe.make_loader_shape(cfg.V, cfg.L, cfg.E, [cfg.d_model * cfg.d_ff] * cfg.mats, cfg.dtype, cfg.capacity)
+    dev = [[to_dev(m) for m in mats] for mats in variants]
+    torch.cuda.synchronize()
+    es = 2 if cfg.dtype == "bf16" else 4
+    nbytes = cfg.V * cfg.L * cfg.E * cfg.n_params * es
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * a.steps)]
+    for _ in range(a.warmup):
+        dist = mmoe.expert_distance(sh, dev)
+        out = mmoe.build_expert_map(sh, dist)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        ev[2 * i].record()
+        dist = mmoe.expert_distance(sh, dev)
+        ev[2 * i + 1].record()
+        out = mmoe.build_expert_map(sh, dist)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / a.steps * 1e3
+    dist_ms = float(np.mean([ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(a.steps)]))
+    ach = nbytes / (dist_ms * 1e-3) / 1e9
+    res = {
+        "metric": "expert-map builder (Algorithm 1): bytes of expert weights ranked per second",
+        "value": nbytes / (ms * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "V": cfg.V, "L": cfg.L, "E": cfg.E, "d_model": cfg.d_model, "d_ff": cfg.d_ff,
+                   "matrices_per_expert": cfg.mats, "capacity": cfg.capacity, "seed": cfg.seed,
+                   "expert_bytes_total": nbytes, "host_generation_s": t_gen},
+        "roofline": {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                     "traffic": None, "kernel": "expert_distance_kernel (+ its fixed-order finish)",
+                     "bytes_per_launch": nbytes, "avg_launch_ms": dist_ms},
+    }
+    if not a.no_cpu_baseline:
+        from oracle import table as tab
+
+        # the oracle on a bounded sample of locations (all of them when that takes seconds), then the table
+        n_loc = cfg.L * cfg.E
+        per_loc = cfg.V * cfg.n_params * es
+        sample = n_loc if n_loc * per_loc <= (8 << 30) else max(1, (8 << 30) // per_loc)
+        locs = np.sort(np.random.default_rng(0).choice(n_loc, sample, replace=False))
+        t0 = time.perf_counter()
+        d_ref = np.array([tab.location_distance(
+            [np.concatenate([m[l, e] for m in mats]) for mats in variants], cfg.dtype)
+            for l, e in ((int(x) // cfg.E, int(x) % cfg.E) for x in locs)])
+        t_cpu = time.perf_counter() - t0
+        d_got = dist.cpu().numpy().reshape(-1)
+        res["cpu_baseline"] = {"value": sample * per_loc / t_cpu / 1e9, "unit": "GB/s", "cores": oracle_threads(),
+                               "cpu": cpu_model(), "kind": "oracle",
+                               "sample": f"distances of {sample} of {n_loc} locations ({t_cpu:.2f} s)"}
+        par = {"locations": int(sample), "max_rel_distance_err": float(np.max(np.abs(d_got[locs] - d_ref) / d_ref))}
+        if sample == n_loc:
+            ref = tab.build_table(d_ref.reshape(cfg.L, cfg.E), cfg.V, cfg.capacity)
+            rank, owner, M, S, src = (t.cpu().numpy() for t in out)
+            par.update(rank_bit_equal=bool(np.array_equal(rank, ref["rank"])),
+                       owner_bit_equal=bool(np.array_equal(owner, ref["owner"])),
+                       tables_bit_equal=bool(np.array_equal(M, ref["M"]) and np.array_equal(S, ref["S"])))
+        res["parity"] = par
+    print(json.dumps(res))
+
+
+def oracle_threads():
+    import oracle
+
+    return oracle.threads()
+
+
 def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this layer runs on one GPU; --gpus must be 1 (no sharding, no collectives)", file=sys.stderr)
         sys.exit(2)
+    if a.loader:
+        return bench_loader(a)
     import torch
 
     from paper_2505_06481_amd import mmoe, synth

@@ -258,6 +258,56 @@ int mmoe_expert_plan(const mmoe_shape *shape, int *streaming, int *tile_rows);
 int mmoe_probe_ceilings(void* buf, size_t bytes, float* out, void* stream);
 
 /*
+ * The initial expert loader's table (Algorithm 1; section 3.1), run once, offline, before
+ * serving.  V fine-tuned variants of one MoE model, L layers of E experts; the expert block of
+ * a location (layer, expert) is the concatenation of its n_mats matrices.
+ *   1. degree of similarity of a location: the L2 distance between the flattened experts that
+ *      two variants hold there, summed over all variant-to-variant combinations (unordered pairs;
+ *      the listing's sum over ordered pairs is twice this and ranks identically);
+ *   2. locations are ranked, the lowest distance first (rank 1), ties to the lower l*E + e;
+ *   3. from rank 1 on, while fewer than `capacity` locations are taken, the location is given to
+ *      the variants in turn: rank r goes to variant (r - 1) mod V (the section's text: with two
+ *      models the odd ranks go to the first model; the listing's "count mod |M|" read with
+ *      0-based lists starts one variant later).  Such a location is CONSOLIDATED: one resident
+ *      expert, the owner's, used by every variant;
+ *   4. any other location keeps every variant's own expert (the paper loads it on a miss; here
+ *      it is a private slot of the pool).
+ * The per-layer table of the forward pass follows: variant 0's locations take slots 0..E-1
+ * (shared or private alike), the private slots of variants 1.. follow in (variant, expert) order.
+ */
+typedef struct {
+    int32_t V;            /* variants, 1..8                                             */
+    int32_t L;            /* layers                                                     */
+    int32_t E;            /* experts per layer; L*E <= 4096                             */
+    int32_t n_mats;       /* matrices of an expert block, 1..3                          */
+    int64_t mat_elems[3]; /* elements of each matrix per location, multiples of 256     */
+    int32_t dtype;        /* mmoe_dtype                                                 */
+    int32_t capacity;     /* expert capacity C: locations to consolidate (>= 0)         */
+} mmoe_loader_shape;
+
+/* Host only, pure.  Workspace (bytes) for mmoe_expert_distance, 0 if the shape is invalid. */
+size_t mmoe_loader_workspace_bytes(const mmoe_loader_shape *shape);
+
+/*
+ * Step 1.  `mats` is a HOST array of V*n_mats DEVICE pointers: mats[v*n_mats + m] is matrix m of
+ * variant v for every location, [L, E, mat_elems[m]] row-major, 16-byte aligned.
+ * distance [L, E] float64 (DEVICE) out.  Differences and squares are fp32, sums fp64, in a fixed
+ * order (no atomics).  Reads every stored element once.  Uses `ws`.
+ */
+int mmoe_expert_distance(const mmoe_loader_shape *shape, const void *const *mats, double *distance,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Steps 2 to 4, all DEVICE pointers.  distance [L, E] float64 in (finite).  Out: rank [L, E] int32
+ * (1-based); owner [L, E] int32 (variant of a consolidated location, -1 otherwise); M [L, V, E]
+ * int32 (the layer's table for mmoe_layer_forward); S [L] int32 (slots of each layer's pool);
+ * slot_src [L, V*E, 2] int32: (variant, expert) whose weights fill each slot of the layer's pool,
+ * rows past S[l] are (-1, -1).
+ */
+int mmoe_build_expert_map(const mmoe_loader_shape *shape, const double *distance, int32_t *rank,
+                          int32_t *owner, int32_t *M, int32_t *S, int32_t *slot_src, void *stream);
+
+/*
  * Debugging aid, SYNCHRONISES the stream: checks on the device that every vid[t] is in
  * [0,V) and every M[v][e] in [0,S).  Returns 0 if so, 1 if not, a negative status on
  * argument errors.  `ws` needs 256 bytes.

@@ -304,6 +304,53 @@ int mmoe_probe_ceilings(void* buf, size_t bytes, float* out, void* stream)
     return run_probe(buf, bytes, out, (hipStream_t)stream);
 }
 
+static int check_loader_shape(const mmoe_loader_shape* s)
+{
+    if (!s) return MMOE_ERR_NULL;
+    if (s->V <= 0 || s->L <= 0 || s->E <= 0 || s->n_mats <= 0 || s->capacity < 0) return MMOE_ERR_DIM;
+    if (s->dtype != MMOE_F32 && s->dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
+    if (s->V > kLoaderMaxV || s->n_mats > 3 || (int64_t)s->L * s->E > kLoaderMaxLoc) return MMOE_ERR_LIMIT;
+    for (int m = 0; m < s->n_mats; ++m) {
+        if (s->mat_elems[m] <= 0) return MMOE_ERR_DIM;
+        if (s->mat_elems[m] % 256 != 0) return MMOE_ERR_MULTIPLE;
+        if (s->mat_elems[m] > ((int64_t)1 << 40)) return MMOE_ERR_LIMIT;
+    }
+    return MMOE_OK;
+}
+
+size_t mmoe_loader_workspace_bytes(const mmoe_loader_shape* shape)
+{
+    if (check_loader_shape(shape) != MMOE_OK) return 0;
+    return loader_ws_bytes(*shape);
+}
+
+int mmoe_expert_distance(const mmoe_loader_shape* shape, const void* const* mats, double* distance, void* ws,
+                         size_t ws_bytes, void* stream)
+{
+    int rc = check_loader_shape(shape);
+    if (rc) return rc;
+    if (!mats || !distance) return MMOE_ERR_NULL;
+    for (int i = 0; i < shape->V * shape->n_mats; ++i) {
+        if (!mats[i]) return MMOE_ERR_NULL;
+        if (misaligned(mats[i], 16)) return MMOE_ERR_ALIGN;
+    }
+    if (!ws || ws_bytes < loader_ws_bytes(*shape)) return MMOE_ERR_WORKSPACE;
+    if (misaligned(ws, 256) || misaligned(distance, 8)) return MMOE_ERR_ALIGN;
+    return launch_expert_distance(*shape, mats, distance, (double*)ws, (hipStream_t)stream);
+}
+
+int mmoe_build_expert_map(const mmoe_loader_shape* shape, const double* distance, int32_t* rank, int32_t* owner,
+                          int32_t* M, int32_t* S, int32_t* slot_src, void* stream)
+{
+    int rc = check_loader_shape(shape);
+    if (rc) return rc;
+    if (!distance || !rank || !owner || !M || !S || !slot_src) return MMOE_ERR_NULL;
+    if (misaligned(distance, 8) || misaligned(rank, 4) || misaligned(owner, 4) || misaligned(M, 4) ||
+        misaligned(S, 4) || misaligned(slot_src, 4))
+        return MMOE_ERR_ALIGN;
+    return launch_expert_map(*shape, distance, rank, owner, M, S, slot_src, (hipStream_t)stream);
+}
+
 int mmoe_validate_inputs(const mmoe_shape* shape, const int32_t* vid, const int32_t* M, void* ws,
                          size_t ws_bytes, void* stream)
 {

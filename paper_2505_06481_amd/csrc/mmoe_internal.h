@@ -14,6 +14,8 @@ constexpr int kMaxTopK = 8;
 constexpr int kMaxE = 256;
 constexpr int kMaxS = 1024;
 constexpr int kPermChunk = 2048;  // pairs per workgroup in the grouping kernels
+constexpr int kLoaderMaxV = 8;       // variants the expert-map builder compares in one pass
+constexpr int kLoaderMaxLoc = 4096;  // expert locations (layers x experts) it ranks
 
 typedef __bf16 bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -84,6 +86,13 @@ int launch_pack(const mmoe_shape& s, const void* W1, const void* W3, const void*
                 void* W2p, hipStream_t st);
 int run_probe(void* buf, size_t bytes, float* out, hipStream_t st);
 int launch_validate(const mmoe_shape& s, const int32_t* vid, const int32_t* M, int32_t* flag, hipStream_t st);
+
+// expert-map builder (one translation unit)
+size_t loader_ws_bytes(const mmoe_loader_shape& s);
+int launch_expert_distance(const mmoe_loader_shape& s, const void* const* mats, double* distance, double* partial,
+                           hipStream_t st);
+int launch_expert_map(const mmoe_loader_shape& s, const double* distance, int32_t* rank, int32_t* owner, int32_t* M,
+                      int32_t* S, int32_t* slot_src, hipStream_t st);
 
 inline int launch_status()
 {

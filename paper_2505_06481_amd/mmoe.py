@@ -28,7 +28,8 @@ _TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
 EXPORTS = [
     "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
     "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_layer_forward_events",
-    "mmoe_layer_forward_static", "mmoe_validate_inputs", "mmoe_probe_ceilings", "mmoe_expert_plan",
+    "mmoe_layer_forward_static", "mmoe_loader_workspace_bytes", "mmoe_expert_distance", "mmoe_build_expert_map",
+    "mmoe_validate_inputs", "mmoe_probe_ceilings", "mmoe_expert_plan",
 ]
 
 
@@ -51,6 +52,17 @@ def make_shape(T, d_model, d_ff, V, E, S, top_k, dtype, act, tile_rows=0, gate="
     ac = _ACTS[act] if isinstance(act, str) else int(act)
     ga = _GATES[gate] if isinstance(gate, str) else int(gate)
     return Shape(T, d_model, d_ff, V, E, S, top_k, dt, ac, ga, tile_rows)
+
+
+class LoaderShape(ctypes.Structure):
+    _fields_ = [("V", ctypes.c_int32), ("L", ctypes.c_int32), ("E", ctypes.c_int32), ("n_mats", ctypes.c_int32),
+                ("mat_elems", ctypes.c_int64 * 3), ("dtype", ctypes.c_int32), ("capacity", ctypes.c_int32)]
+
+
+def make_loader_shape(V, L, E, mat_elems, dtype, capacity) -> LoaderShape:
+    dt = _DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
+    me = list(mat_elems) + [0] * (3 - len(mat_elems))
+    return LoaderShape(V, L, E, len(mat_elems), (ctypes.c_int64 * 3)(*me), dt, capacity)
 
 
 _lib = None
@@ -80,10 +92,16 @@ def lib():
         L.mmoe_layer_forward_events.argtypes = [sp] + [vp] * 10 + [sz, vp, vp]
         L.mmoe_layer_forward_static.argtypes = [sp] + [vp] * 10
         L.mmoe_validate_inputs.argtypes = [sp, vp, vp, vp, sz, vp]
+        lp = ctypes.POINTER(LoaderShape)
+        L.mmoe_loader_workspace_bytes.restype = sz
+        L.mmoe_loader_workspace_bytes.argtypes = [lp]
+        L.mmoe_expert_distance.argtypes = [lp, ctypes.POINTER(vp), vp, vp, sz, vp]
+        L.mmoe_build_expert_map.argtypes = [lp] + [vp] * 7
         L.mmoe_expert_plan.argtypes = [sp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.mmoe_probe_ceilings.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_float), vp]
         for n in EXPORTS[2:]:
-            getattr(L, n).restype = i
+            if n != "mmoe_loader_workspace_bytes":
+                getattr(L, n).restype = i
         _lib = L
     return _lib
 
@@ -256,3 +274,36 @@ def expert_plan(shape: Shape):
     _check(lib().mmoe_expert_plan(ctypes.byref(shape), ctypes.byref(streaming), ctypes.byref(rows)),
            "mmoe_expert_plan")
     return bool(streaming.value), int(rows.value)
+
+
+def expert_distance(shape: LoaderShape, mats):
+    """``mats[v][m]``: device tensor [L, E, mat_elems[m]] of variant v.  Returns distance [L, E] float64."""
+    dt = _TORCH_DT[shape.dtype]
+    n = shape.V * shape.n_mats
+    ptrs = (ctypes.c_void_p * n)()
+    for v in range(shape.V):
+        for m in range(shape.n_mats):
+            ptrs[v * shape.n_mats + m] = _ptr(mats[v][m], dt, shape.L * shape.E * shape.mat_elems[m], f"mats[{v}][{m}]")
+    dev = mats[0][0].device
+    need = int(lib().mmoe_loader_workspace_bytes(ctypes.byref(shape)))
+    if need == 0:
+        raise MmoeError(int(lib().mmoe_expert_distance(ctypes.byref(shape), ptrs, None, None, 0, None)),
+                        "mmoe_loader_workspace_bytes")
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    dist = torch.empty((shape.L, shape.E), dtype=torch.float64, device=dev)
+    _check(lib().mmoe_expert_distance(ctypes.byref(shape), ptrs, _ptr(dist), _ptr(ws), ws.numel(), _stream()),
+           "mmoe_expert_distance")
+    return dist
+
+
+def build_expert_map(shape: LoaderShape, distance):
+    """Returns (rank [L,E], owner [L,E], M [L,V,E], S [L], slot_src [L, V*E, 2]), int32 device tensors."""
+    dev = distance.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    V, L, E = shape.V, shape.L, shape.E
+    rank, owner = torch.empty((L, E), **i32), torch.empty((L, E), **i32)
+    M, S, src = torch.empty((L, V, E), **i32), torch.empty(L, **i32), torch.empty((L, V * E, 2), **i32)
+    _check(lib().mmoe_build_expert_map(ctypes.byref(shape), _ptr(distance, torch.float64, L * E, "distance"),
+                                       _ptr(rank), _ptr(owner), _ptr(M), _ptr(S), _ptr(src), _stream()),
+           "mmoe_build_expert_map")
+    return rank, owner, M, S, src

@@ -1,0 +1,133 @@
+"""GPU parity of the expert-map builder (Algorithm 1, section 3.1) through the C ABI: the distances
+against the oracle's float64 values, every integer output (ranks, owners, per-layer tables, slot
+sources) bit for bit, and the emitted table driving the layer's forward pass."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_06481_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mm():
+    from paper_2505_06481_amd import mmoe
+    mmoe.lib()
+    assert torch.cuda.is_available()
+    return mmoe
+
+
+def upload(variants):
+    import gpu_common as gc
+    return [[gc.to_dev(m, None) for m in mats] for mats in variants]
+
+
+def run_builder(mm, cfg, variants):
+    sh = mm.make_loader_shape(cfg.V, cfg.L, cfg.E, [cfg.d_model * cfg.d_ff] * cfg.mats, cfg.dtype, cfg.capacity)
+    dev = upload(variants)
+    dist = mm.expert_distance(sh, dev)
+    out = mm.build_expert_map(sh, dist)
+    torch.cuda.synchronize()
+    return sh, dev, dist, out
+
+
+def check_against_oracle(mm, cfg, variants):
+    from oracle import table as tab
+    print(f"case {cfg.name} V={cfg.V} L={cfg.L} E={cfg.E} d={cfg.d_model} f={cfg.d_ff} {cfg.dtype} C={cfg.capacity}",
+          flush=True)
+    sh, dev, dist, (rank, owner, M, S, src) = run_builder(mm, cfg, variants)
+    d_ref = tab.distances(variants, cfg.dtype)
+    d_got = dist.cpu().numpy()
+    # fp32 differences and squares, float64 sums: far inside the gaps between neighbouring ranks
+    np.testing.assert_allclose(d_got, d_ref, rtol=2e-7)
+    gaps = np.diff(np.sort(d_ref.reshape(-1)))
+    if (gaps > 0).any():    # exact ties are decided by the location index on both sides
+        assert gaps[gaps > 0].min() > 50 * np.abs(d_got - d_ref).max(), "ranking not decided by the data"
+    ref = tab.build_table(d_ref, cfg.V, cfg.capacity)
+    assert np.array_equal(rank.cpu().numpy(), ref["rank"])
+    assert np.array_equal(owner.cpu().numpy(), ref["owner"])
+    assert np.array_equal(M.cpu().numpy(), ref["M"])
+    assert np.array_equal(S.cpu().numpy(), ref["S"])
+    src = src.cpu().numpy()
+    for l in range(cfg.L):
+        n = int(ref["S"][l])
+        assert np.array_equal(src[l, :n], ref["slot_src"][l]) and (src[l, n:] == -1).all()
+    # the same call twice: deterministic bit for bit
+    _, _, dist2, _ = run_builder(mm, cfg, variants)
+    assert torch.equal(dist, dist2)
+    return ref, dev
+
+
+SMALL = [
+    synth.TableConfig("tb_v2_bf16", 2, 3, 4, 256, 512, "swiglu", "bf16", capacity=5, seed=1),
+    synth.TableConfig("tb_v3_f32", 3, 2, 5, 256, 256, "relu", "f32", capacity=4, seed=2),
+    synth.TableConfig("tb_v4_bf16_ragged_chunks", 4, 2, 3, 768, 768, "gelu", "bf16", capacity=6, seed=3),   # not a whole number of chunks
+    synth.TableConfig("tb_v8", 8, 1, 4, 256, 256, "relu", "bf16", capacity=3, seed=4),
+    synth.TableConfig("tb_v1", 1, 2, 2, 256, 256, "relu", "f32", capacity=2, seed=5),                        # no pair at all
+    synth.TableConfig("tb_none", 2, 2, 4, 256, 256, "relu", "bf16", capacity=0, seed=6),
+    synth.TableConfig("tb_all", 3, 2, 4, 256, 256, "swiglu", "bf16", capacity=100, seed=7),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
+def test_small_tables(mm, oracle, cfg):
+    check_against_oracle(mm, cfg, synth.make_variants(cfg))
+
+
+def test_exact_ties_rank_by_location(mm, oracle):
+    cfg = synth.TableConfig("tb_ties", 2, 2, 3, 256, 256, "relu", "f32", capacity=3, seed=8)
+    variants = synth.make_variants(cfg)
+    for v in range(cfg.V):                       # locations (0,0), (0,2) and (1,1) get identical experts
+        for m in range(cfg.mats):
+            variants[v][m][0, 2] = variants[v][m][0, 0]
+            variants[v][m][1, 1] = variants[v][m][0, 0]
+    ref, _ = check_against_oracle_ties(mm, cfg, variants)
+    assert ref["rank"][0, 0] < ref["rank"][0, 2] < ref["rank"][1, 1]
+
+
+def check_against_oracle_ties(mm, cfg, variants):
+    from oracle import table as tab
+    sh, dev, dist, (rank, owner, M, S, src) = run_builder(mm, cfg, variants)
+    d_got = dist.cpu().numpy()
+    assert d_got[0, 0] == d_got[0, 2] == d_got[1, 1]          # identical data, identical sums
+    d_ref = tab.distances(variants, cfg.dtype)
+    ref = tab.build_table(d_ref, cfg.V, cfg.capacity)
+    assert np.array_equal(rank.cpu().numpy(), ref["rank"]) and np.array_equal(owner.cpu().numpy(), ref["owner"])
+    return ref, dev
+
+
+def test_switch_family_table_at_full_size(mm, oracle):
+    """The paper's scalability scenario (section 4.3): Switch-Base-8, all 12 MoE layers, 4 variants."""
+    cfg = synth.TABLE_CONFIGS["switch8_table_v4_l12"]
+    ref, _ = check_against_oracle(mm, cfg, synth.make_variants(cfg))
+    assert int((ref["owner"] >= 0).sum()) == 48
+    assert [int((ref["owner"] == v).sum()) for v in range(4)] == [12, 12, 12, 12]     # equally representative
+
+
+def test_emitted_table_drives_the_layer(mm, oracle):
+    """One layer of a built model: the pool assembled from slot_src, the layer run with the emitted
+    table, against the oracle's layer on the oracle's own table and pool."""
+    import gpu_common as gc
+    cfg = synth.TableConfig("tb_layer", 3, 2, 4, 256, 512, "swiglu", "bf16", capacity=5, seed=9)
+    variants = synth.make_variants(cfg)
+    ref, dev = check_against_oracle(mm, cfg, variants)
+    sh, _, dist, (rank, owner, M, S, src) = run_builder(mm, cfg, variants)
+    layer = 1
+    S_l = int(S[layer])
+    src_l = src[layer, :S_l].cpu().numpy()
+    d, f = cfg.d_model, cfg.d_ff
+    # pool assembly is a copy of stored weights (no arithmetic): slot s <- expert src_l[s] of the layer
+    pool = [np.stack([variants[v][m][layer, e] for v, e in src_l]).reshape(S_l, *shp)
+            for m, shp in ((0, (d, f)), (1, (d, f)), (2, (f, d)))]
+    lcfg = synth.Config("tb_layer_fwd", 200, d, f, cfg.V, cfg.E, 2, "bf16", "swiglu", seed=10)
+    inp = synth.make_inputs(lcfg, weights=False)
+    inp.update(M=ref["M"][layer].copy(), S=S_l, W1=pool[0], W3=pool[1], W2=pool[2])
+    shape = mm.make_shape(lcfg.T, d, f, cfg.V, cfg.E, S_l, 2, "bf16", "swiglu")
+    W1p, W3p, W2p = mm.pack_weights(shape, *(gc.to_dev(p, None) for p in pool))
+    Y = mm.layer_forward(shape, gc.to_dev(inp["X"], None), torch.from_numpy(inp["vid"]).cuda(),
+                         gc.to_dev(inp["Wr"], None), None, M[layer].contiguous(), W1p, W3p, W2p,
+                         mm.alloc_workspace(shape))
+    torch.cuda.synchronize()
+    want = oracle.layer_forward(inp, 2, "bf16", "swiglu")
+    gc.assert_close(gc.to_np64(Y), want["Y"], "bf16", "layer on the emitted table")

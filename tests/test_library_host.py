@@ -90,6 +90,28 @@ def test_bad_arguments_become_error_codes(mm):
     assert mm.strerror(-99) == "unknown status"
 
 
+def test_expert_map_builder_argument_checks(mm):
+    L = mm.lib()
+    p = ctypes.c_void_p(4096)
+    ok = mm.make_loader_shape(2, 3, 4, [256 * 512] * 2, "bf16", 5)
+    ptrs = (ctypes.c_void_p * 4)(4096, 4096, 4096, 4096)
+    need = L.mmoe_loader_workspace_bytes(ctypes.byref(ok))
+    assert need >= 3 * 4 * 2 * 8                               # a partial sum per location and chunk
+    assert L.mmoe_expert_distance(ctypes.byref(ok), ptrs, p, p, 16, None) == -6          # workspace too small
+    assert L.mmoe_expert_distance(ctypes.byref(ok), None, p, p, need, None) == -1
+    bad = (ctypes.c_void_p * 4)(4096, 4100, 4096, 4096)
+    assert L.mmoe_expert_distance(ctypes.byref(ok), bad, p, p, need, None) == -7          # misaligned matrix
+    for shape, code in ((mm.make_loader_shape(9, 3, 4, [256], "bf16", 1), -9),           # more than 8 variants
+                        (mm.make_loader_shape(2, 100, 100, [256], "bf16", 1), -9),       # more than 4096 locations
+                        (mm.make_loader_shape(2, 3, 4, [100], "bf16", 1), -8),           # not a multiple of 256
+                        (mm.make_loader_shape(2, 3, 4, [256], "bf16", -1), -2),          # negative capacity
+                        (mm.make_loader_shape(2, 0, 4, [256], "bf16", 1), -2),
+                        (mm.make_loader_shape(2, 3, 4, [256], 7, 1), -4)):
+        assert L.mmoe_loader_workspace_bytes(ctypes.byref(shape)) == 0
+        assert L.mmoe_build_expert_map(ctypes.byref(shape), p, p, p, p, p, p, None) == code
+    assert L.mmoe_build_expert_map(ctypes.byref(ok), p, p, None, p, p, p, None) == -1
+
+
 def test_binding_refuses_host_tensors(mm):
     import torch
     sh = mm.make_shape(4, 256, 256, 1, 2, 2, 1, "f32", "relu")
