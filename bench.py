@@ -74,6 +74,10 @@ def parse():
                     help="after the main workload (Mixtral-shaped pools only): the layer at 1, 2, 4, ... 64 tokens on "
                          "the same pool, with the weight bytes of the slots each batch touches and the fraction of "
                          "HBM peak over the whole layer")
+    ap.add_argument("--miss-sweep", action="store_true",
+                    help="after the main workload: one decode token on the same pool with 0, 1 and 2 of its two "
+                         "experts held in pinned host memory instead of HBM (the paper's per-layer latency by hit "
+                         "rate: the miss path of Algorithm 2)")
     ap.add_argument("--loader", default=None, metavar="TABLE_WORKLOAD",
                     help="instead of the layer: time the expert-map builder (Algorithm 1) on one of "
                          "synth.TABLE_CONFIGS; one step = distances of every expert location + ranking + tables")
@@ -181,6 +185,56 @@ def run_workload(cfg, inp, pool, steps, warmup):
     return dict(ms_per_step=wall / steps * 1e3, up_ms=float(up_ms.mean()), stages_ms=stages, counts=counts, S=S, Y=Y,
                 topk_idx=idx.cpu().numpy(), perm=sl[3].cpu().numpy(),
                 events_ms={"median": float(np.median(per_step)), "min": float(per_step.min())})
+
+
+def miss_sweep(cfg, inp, pool, shape, steps):
+    """One token, its top-k experts in k slots: the whole layer (gate, map lookup, host
+    synchronisation, copies of the missing experts from pinned host memory, experts, combination)
+    with 0 .. k of those slots not resident.  Host clock around `steps` calls, each ending in a
+    stream synchronisation."""
+    import torch
+
+    from paper_2505_06481_amd import mmoe, synth
+
+    tcfg = cfg.replace(name=cfg.name + "_T1", T=1, vid_mode="uniform", bias_alpha=0.0)
+    tinp = synth.make_inputs(tcfg, weights=False)
+    S = int(inp["S"])
+    sh = mmoe.make_shape(1, cfg.d_model, cfg.d_ff, cfg.V, cfg.E, S, cfg.top_k, cfg.dtype, cfg.act, gate=cfg.gate)
+    X, Wr = to_dev(tinp["X"]), to_dev(tinp["Wr"])
+    vid, M = torch.from_numpy(tinp["vid"]).cuda(), torch.from_numpy(inp["M"]).cuda()
+    ws = mmoe.alloc_workspace(sh)
+    idx = mmoe.route(sh, X, vid, Wr, None)[0]
+    slots = [int(inp["M"][int(tinp["vid"][0]), int(e)]) for e in idx[0].cpu().numpy()]
+    W1p, W3p, W2p = pool
+    host = []
+    for p in (W1p, W3p, W2p):
+        host.append(None if p is None else
+                    [p.view(S, -1)[s].cpu().pin_memory() if s in slots else None for s in range(S)])
+    copy_stream = torch.cuda.Stream()
+    mats = 3 if W3p is not None else 2
+    expert_bytes = mats * cfg.d_model * cfg.d_ff * (2 if cfg.dtype == "bf16" else 4)
+    rows, base_ms = [], None
+    for missing in range(len(set(slots)) + 1):
+        gone = set(slots[len(slots) - missing:]) if missing else set()
+        resident = [s not in gone for s in range(S)]
+        for _ in range(3):
+            mmoe.layer_forward_paged(sh, X, vid, Wr, None, M, W1p, W3p, W2p, resident, host, ws, copy_stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            _, fetched = mmoe.layer_forward_paged(sh, X, vid, Wr, None, M, W1p, W3p, W2p, resident, host, ws, copy_stream)
+            torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        assert sum(fetched) == len(gone)
+        base_ms = ms if missing == 0 else base_ms
+        row = {"experts_missing": missing, "of": len(slots), "ms_per_layer": ms}
+        if missing:
+            row["ms_per_missing_expert"] = (ms - base_ms) / missing
+            row["host_to_device_GBps"] = missing * expert_bytes / ((ms - base_ms) * 1e-3) / 1e9
+        rows.append(row)
+    return {"tokens": 1, "expert_bytes": expert_bytes, "rows": rows,
+            "note": "paper, one A100 over PCIe Gen4 (section 5.1, per-layer latency by hit rate): "
+                    "1.2 / 29.2 / 56.8 ms with 2 / 1 / 0 experts resident, 27.8 ms per missing expert"}
 
 
 def stage_rates(cfg, stages):
@@ -448,6 +502,9 @@ def main():
                           "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                           "stages_ms": sres["stages_ms"]})
         out["decode_sweep"] = sweep
+
+    if a.miss_sweep:
+        out["miss_path"] = miss_sweep(cfg, inp, pool, shape, max(a.steps, 20))
 
     if not a.no_ceilings:
         # what this GPU delivers with nothing else in the way: a pure streaming read and a pure

@@ -194,6 +194,31 @@ int mmoe_layer_forward(const mmoe_shape *shape, const void *X, const int32_t *vi
                        const void *W2p, void *Y, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The layer with part of the pool in host memory: Algorithm 2's miss branch (section 3.2: on a
+ * miss the requested variant's own expert is loaded from the host; section 5.1: the copy is what a
+ * miss costs).  resident[s] (HOST array of S flags) says whether slot s of the DEVICE pool holds
+ * its expert; for every other slot host_W1p[s], host_W3p[s], host_W2p[s] (HOST arrays of S
+ * pointers) point to the slot's PACKED matrices in PINNED host memory (the layout
+ * mmoe_pack_weights writes, one slot each).  The call
+ *   - runs the gate, the map lookup and the grouping, then SYNCHRONISES `stream` once to learn
+ *     which slots the batch touches (the copies to issue depend on the routing);
+ *   - copies every touched non-resident slot into its place in the device pool on `copy_stream`
+ *     (a second stream of the default priority, not `stream`);
+ *   - applies the resident experts to their groups while the copies run, then the fetched ones,
+ *     and combines: Y is bit-identical to mmoe_layer_forward on a fully resident pool.
+ * The pool's non-resident slots are scratch until fetched; a fetched slot stays valid afterwards,
+ * and fetched[s] (HOST out, may be NULL) tells the caller which ones arrived, so that it can mark
+ * them resident for later calls (the paper leaves open what is evicted).  Returns the number
+ * of slots fetched (>= 0) or a negative status.  Everything queued on `stream` before the call may
+ * still read the pool: the copies wait for it.
+ */
+int mmoe_layer_forward_paged(const mmoe_shape *shape, const void *X, const int32_t *vid, const void *Wr,
+                             const float *br, const int32_t *M, void *W1p, void *W3p, void *W2p,
+                             const uint8_t *resident, const void *const *host_W1p,
+                             const void *const *host_W3p, const void *const *host_W2p, void *Y, void *ws,
+                             size_t ws_bytes, void *stream, void *copy_stream, uint8_t *fetched);
+
+/*
  * mmoe_layer_forward for callers that cannot allocate device memory or hand over a workspace:
  * code that runs under HIP graph capture, tight serving loops (one decode step after the
  * other), harnesses that forbid allocation.  Same arguments without `ws`; same kernels, same

@@ -72,12 +72,17 @@ struct RowSet {
 
 __device__ __forceinline__ RowSet slot_rows(const int32_t* __restrict__ offsets, const int32_t* __restrict__ perm,
                                             int kdiv, const int32_t* __restrict__ slot_of_pair, int P, int s,
-                                            int* mine, int* mine_cnt)
+                                            int* mine, int* mine_cnt, SlotFilter filt)
 {
     RowSet rs;
     rs.perm = perm;
     rs.kdiv = kdiv;
     rs.mine = nullptr;
+    if (filt.skips(s)) {  // uniform over the workgroup: this launch leaves the slot to another one
+        rs.r0 = 0;
+        rs.cnt = 0;
+        return rs;
+    }
     if (!slot_of_pair) {
         rs.r0 = offsets[s];
         rs.cnt = offsets[s + 1] - rs.r0;
@@ -107,7 +112,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
                                                             const int32_t* __restrict__ offsets,
                                                             const int32_t* __restrict__ slot_of_pair, int P,
                                                             const T* __restrict__ W0, const T* __restrict__ W1,
-                                                            void* __restrict__ out, int K, int N)
+                                                            void* __restrict__ out, int K, int N, SlotFilter filt)
 {
     constexpr int EPB = 16 / (int)sizeof(T);  // elements per 16-byte piece
     constexpr int KSS = 16 * EPB;             // elements per 256-byte step
@@ -117,7 +122,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
 
     const int s = blockIdx.y;
     const int n0 = blockIdx.x * 16;
-    const RowSet rs = slot_rows(offsets, perm, kdiv, slot_of_pair, P, s, mine, &mine_cnt);
+    const RowSet rs = slot_rows(offsets, perm, kdiv, slot_of_pair, P, s, mine, &mine_cnt, filt);
     const int cnt = rs.cnt;
     if (cnt <= 0) return;  // uniform over the workgroup
 
@@ -254,7 +259,8 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
                                                                  const int32_t* __restrict__ slot_of_pair, int P,
                                                                  const uint16_t* __restrict__ W0,
                                                                  const uint16_t* __restrict__ W1,
-                                                                 void* __restrict__ out, int K, int N)
+                                                                 void* __restrict__ out, int K, int N,
+                                                                 SlotFilter filt)
 {
     __shared__ float red[kSkWaves][NW][kWave][16];  // 16 KB per matrix
     __shared__ int mine[kSelfMaxP];
@@ -262,7 +268,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
 
     const int s = blockIdx.y;
     const int nb = blockIdx.x;
-    const RowSet rs = slot_rows(offsets, perm, kdiv, slot_of_pair, P, s, mine, &mine_cnt);
+    const RowSet rs = slot_rows(offsets, perm, kdiv, slot_of_pair, P, s, mine, &mine_cnt, filt);
     const int cnt = rs.cnt;
     if (cnt <= 0) return;  // uniform over the workgroup
 
@@ -373,8 +379,8 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
 }
 
 static int run_skinny_bf16(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
-                           const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
-                           hipEvent_t mid)
+                           const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H,
+                           float* Yg, hipStream_t st, hipEvent_t mid, SlotFilter filt)
 {
     const int32_t* noperm = nullptr;
     const int d = s.d_model, f = s.d_ff, P = s.T * s.top_k;
@@ -383,23 +389,23 @@ static int run_skinny_bf16(const mmoe_shape& s, const void* rows, const int32_t*
     const uint16_t* nul = nullptr;
     if (s.act == MMOE_SWIGLU)
         hipLaunchKernelGGL((skinny_frag_kernel<2, 1, kModeSwigluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
-                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f);
+                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, filt);
     else if (s.act == MMOE_GELU)
         hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeGeluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
-                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f);
+                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f, filt);
     else
         hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeReluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
-                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f);
+                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f, filt);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
     hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModePlainF32>), g2, block, 0, st, (const uint16_t*)H, noperm, 1,
-                       offsets, slot_of_pair, P, (const uint16_t*)W2p, nul, (void*)Yg, f, d);
+                       offsets, slot_of_pair, P, (const uint16_t*)W2p, nul, (void*)Yg, f, d, filt);
     return launch_status();
 }
 
 template <typename T>
 static int run_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
-                      const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, hipStream_t st,
-                      hipEvent_t mid)
+                      const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg,
+                      hipStream_t st, hipEvent_t mid, SlotFilter filt)
 {
     const int32_t* noperm = nullptr;
     const int d = s.d_model, f = s.d_ff, P = s.T * s.top_k;
@@ -408,16 +414,16 @@ static int run_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm
     const T* nul = nullptr;
     if (s.act == MMOE_SWIGLU)
         hipLaunchKernelGGL((skinny_kernel<T, 2, 1, kModeSwigluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
-                           offsets, slot_of_pair, P, (const T*)W1p, (const T*)W3p, H, d, f);
+                           offsets, slot_of_pair, P, (const T*)W1p, (const T*)W3p, H, d, f, filt);
     else if (s.act == MMOE_GELU)
         hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeGeluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
-                           offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f);
+                           offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt);
     else
         hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
-                           offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f);
+                           offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
     hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModePlainF32>), g2, block, 0, st, (const T*)H, noperm, 1,
-                       offsets, slot_of_pair, P, (const T*)W2p, nul, (void*)Yg, f, d);
+                       offsets, slot_of_pair, P, (const T*)W2p, nul, (void*)Yg, f, d, filt);
     return launch_status();
 }
 
@@ -428,12 +434,12 @@ bool self_grouping(const mmoe_shape& s)
 
 int launch_ffn_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                       const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H,
-                      float* Yg, hipStream_t st, hipEvent_t mid)
+                      float* Yg, hipStream_t st, hipEvent_t mid, SlotFilter filt)
 {
     if (slot_of_pair && (int64_t)s.T * s.top_k > kSelfMaxP) return MMOE_ERR_LIMIT;
     if (s.dtype == MMOE_BF16)
-        return run_skinny_bf16(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid);
-    return run_skinny<float>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid);
+        return run_skinny_bf16(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt);
+    return run_skinny<float>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt);
 }
 
 }  // namespace mmoe

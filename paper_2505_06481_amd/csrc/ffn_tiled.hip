@@ -51,9 +51,9 @@ __device__ __forceinline__ float silu_mul_t(float g, float u)
 
 __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restrict__ offsets,
                                                          int32_t* __restrict__ tab, int S, int nt_up, int nt_down,
-                                                         int bm, TileLists L)
+                                                         int bm, TileLists L, SlotFilter filt)
 {
-    build_tile_lists(offsets, tab, S, nt_up, nt_down, bm, L);
+    build_tile_lists(offsets, tab, S, nt_up, nt_down, bm, L, filt);
 }
 
 template <int MODE, int BM>
@@ -440,7 +440,7 @@ TileJob tile_job(const mmoe_shape& s, int32_t* tab)
 
 int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
-                     hipStream_t st, hipEvent_t mid, bool tab_ready)
+                     hipStream_t st, hipEvent_t mid, bool tab_ready, SlotFilter filt)
 {
     if (s.dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     const int P = s.T * s.top_k, d = s.d_model, f = s.d_ff;
@@ -450,7 +450,8 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
     const int bm = planned_tile_rows(s);
     const TileLists L = tile_lists(P, s.S, nt_up, nt_down, bm);
     if (!tab_ready)
-        hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, bm, L);
+        hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, bm, L,
+                           filt);
     bool event_failed = false;
     if (bm == kBMBig)
         launch_tiled_products<kBMBig>(s, L, rows, perm, W1p, W3p, W2p, H, Yg, tab, nt_up, nt_down, st, mid,

@@ -43,6 +43,7 @@ WsLayout ws_layout(const mmoe_shape& s)
     L.blk_counts = take((size_t)L.nblk * s.S * 4);
     L.blk_base = take((size_t)L.nblk * s.S * 4);
     L.tile_tab = take(tiled_table_bytes(s));
+    L.resident = take((size_t)s.S);
     L.H = take(P * s.d_ff * es);
     L.Yg = take(P * s.d_model * 4);
     L.total = off;
@@ -237,6 +238,98 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
     if ((rc = mark(MMOE_EV_FFN_DOWN))) return rc;
     if ((rc = launch_combine(*shape, Yg, inv_perm, topk_w, Y, st))) return rc;
     return mark(MMOE_EV_COMBINE);
+}
+
+int mmoe_layer_forward_paged(const mmoe_shape* shape, const void* X, const int32_t* vid, const void* Wr,
+                             const float* br, const int32_t* M, void* W1p, void* W3p, void* W2p,
+                             const uint8_t* resident, const void* const* host_W1p, const void* const* host_W3p,
+                             const void* const* host_W2p, void* Y, void* ws, size_t ws_bytes, void* stream,
+                             void* copy_stream, uint8_t* fetched)
+{
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!X || !vid || !Wr || !M || !W1p || !W2p || !Y || !resident || !host_W1p || !host_W2p) return MMOE_ERR_NULL;
+    const bool gated = shape->act == MMOE_SWIGLU;
+    if (gated != (W3p != nullptr) || gated != (host_W3p != nullptr)) return MMOE_ERR_W3;
+    WsLayout L = ws_layout(*shape);
+    if (!ws || ws_bytes < L.total) return MMOE_ERR_WORKSPACE;
+    if (misaligned(ws, 256) || misaligned(X, 16) || misaligned(Wr, 16) || misaligned(W1p, 16) ||
+        misaligned(W3p, 16) || misaligned(W2p, 16) || misaligned(Y, 16) || misaligned(vid, 4) ||
+        misaligned(br, 4) || misaligned(M, 4))
+        return MMOE_ERR_ALIGN;
+    if (!copy_stream || copy_stream == stream) return MMOE_ERR_NULL;  // the copies need a stream of their own
+    const int S = shape->S;
+    for (int s = 0; s < S; ++s)
+        if (!resident[s] && (!host_W1p[s] || !host_W2p[s] || (gated && !host_W3p[s]))) return MMOE_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream, cp = (hipStream_t)copy_stream;
+    char* w = (char*)ws;
+    int32_t* topk_idx = (int32_t*)(w + L.topk_idx);
+    float* topk_w = (float*)(w + L.topk_w);
+    int32_t* counts = (int32_t*)(w + L.counts);
+    int32_t* offsets = (int32_t*)(w + L.offsets);
+    int32_t* perm = (int32_t*)(w + L.perm);
+    int32_t* inv_perm = (int32_t*)(w + L.inv_perm);
+    uint8_t* res_dev = (uint8_t*)(w + L.resident);
+    float* Yg = (float*)(w + L.Yg);
+
+    hipEvent_t ev_start = nullptr, ev_copied = nullptr;
+    if (hipEventCreateWithFlags(&ev_start, hipEventDisableTiming) != hipSuccess) return MMOE_ERR_LAUNCH;
+    if (hipEventCreateWithFlags(&ev_copied, hipEventDisableTiming) != hipSuccess) {
+        hipEventDestroy(ev_start);
+        return MMOE_ERR_LAUNCH;
+    }
+    auto done = [&](int code) {
+        hipEventDestroy(ev_start);
+        hipEventDestroy(ev_copied);
+        return code;
+    };
+    // everything queued on `stream` before this call may still read the pool: the copies wait for it
+    if (hipEventRecord(ev_start, st) != hipSuccess || hipStreamWaitEvent(cp, ev_start, 0) != hipSuccess)
+        return done(MMOE_ERR_LAUNCH);
+    // gate, expert-map lookup, grouping; then the host learns which slots this batch touches
+    if (hipMemcpyAsync(res_dev, resident, (size_t)S, hipMemcpyHostToDevice, st) != hipSuccess)
+        return done(MMOE_ERR_LAUNCH);
+    if ((rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st))) return done(rc);
+    rc = launch_permute(*shape, X, vid, topk_idx, M, (int32_t*)(w + L.slot), counts, offsets, perm, inv_perm, nullptr,
+                        (int32_t*)(w + L.blk_counts), (int32_t*)(w + L.blk_base), L.nblk, st);
+    if (rc) return done(rc);
+    int32_t host_counts[kMaxS];
+    if (hipMemcpyAsync(host_counts, counts, (size_t)S * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return done(MMOE_ERR_LAUNCH);
+    // misses: the requested variant's own expert is brought in from host memory (Algorithm 2's miss
+    // branch), into the slot's place in the pool, on the copy stream
+    const size_t mat_bytes = (size_t)shape->d_model * shape->d_ff * elem_size(shape->dtype);
+    int n_missed = 0;
+    for (int s = 0; s < S; ++s) {
+        const bool miss = !resident[s] && host_counts[s] > 0;
+        if (fetched) fetched[s] = miss ? 1 : 0;
+        if (!miss) continue;
+        ++n_missed;
+        bool ok = hipMemcpyAsync((char*)W1p + s * mat_bytes, host_W1p[s], mat_bytes, hipMemcpyHostToDevice, cp) == hipSuccess;
+        ok = ok && hipMemcpyAsync((char*)W2p + s * mat_bytes, host_W2p[s], mat_bytes, hipMemcpyHostToDevice, cp) == hipSuccess;
+        if (gated)
+            ok = ok && hipMemcpyAsync((char*)W3p + s * mat_bytes, host_W3p[s], mat_bytes, hipMemcpyHostToDevice, cp) == hipSuccess;
+        if (!ok) return done(MMOE_ERR_LAUNCH);
+    }
+    if (n_missed && hipEventRecord(ev_copied, cp) != hipSuccess) return done(MMOE_ERR_LAUNCH);
+    // hits first (they overlap the copies), then the slots that have just arrived
+    const bool tiled = !use_skinny(*shape);
+    int32_t* tile_tab = (int32_t*)(w + L.tile_tab);
+    for (int pass = 0; pass < (n_missed ? 2 : 1); ++pass) {
+        SlotFilter filt;
+        filt.flag = res_dev;
+        filt.want = pass == 0 ? 1 : 0;
+        if (pass == 1 && hipStreamWaitEvent(st, ev_copied, 0) != hipSuccess) return done(MMOE_ERR_LAUNCH);
+        if (!tiled)
+            rc = launch_ffn_skinny(*shape, X, perm, offsets, nullptr, W1p, W3p, W2p, w + L.H, Yg, st, nullptr, filt);
+        else
+            rc = launch_ffn_tiled(*shape, X, perm, offsets, W1p, W3p, W2p, w + L.H, Yg, tile_tab, st, nullptr, false,
+                                  filt);
+        if (rc) return done(rc);
+    }
+    if ((rc = launch_combine(*shape, Yg, inv_perm, topk_w, Y, st))) return done(rc);
+    return done(n_missed);
 }
 
 int mmoe_layer_forward(const mmoe_shape* shape, const void* X, const int32_t* vid, const void* Wr,

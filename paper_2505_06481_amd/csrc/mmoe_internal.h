@@ -37,9 +37,18 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x)
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline size_t elem_size(int dtype) { return dtype == MMOE_BF16 ? 2 : 4; }
 
+// Which slots one launch of the expert stage works on: all of them (`flag` null), or those whose
+// flag equals `want` (a launch for the resident slots, a later one for the slots just fetched).
+struct SlotFilter {
+    const uint8_t* flag = nullptr;  // DEVICE [S]
+    int want = 0;
+    __host__ __device__ bool skips(int s) const { return flag && flag[s] != want; }
+};
+
 // Sub-buffers of the caller's workspace used by mmoe_layer_forward (byte offsets).
 struct WsLayout {
-    size_t topk_idx, topk_w, slot, counts, offsets, perm, inv_perm, blk_counts, blk_base, tile_tab, H, Yg, total;
+    size_t topk_idx, topk_w, slot, counts, offsets, perm, inv_perm, blk_counts, blk_base, tile_tab, resident, H, Yg,
+        total;
     int nblk;
 };
 WsLayout ws_layout(const mmoe_shape& s);
@@ -69,14 +78,15 @@ int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const
 // indexed by pair id; `perm` and `offsets` are then unused.
 int launch_ffn_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                       const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H,
-                      float* Yg, hipStream_t st, hipEvent_t mid = nullptr);
+                      float* Yg, hipStream_t st, hipEvent_t mid = nullptr, SlotFilter filt = SlotFilter());
 // true when the fused layer skips the grouping kernels (streaming expert kernels, few pairs)
 bool self_grouping(const mmoe_shape& s);
 // `tab`: tiled_table_bytes() of scratch for the row-tile table.
 // `tab_ready`: the grouping kernels have already written the tile lists into `tab`.
 int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
-                     hipStream_t st, hipEvent_t mid = nullptr, bool tab_ready = false);
+                     hipStream_t st, hipEvent_t mid = nullptr, bool tab_ready = false,
+                     SlotFilter filt = SlotFilter());
 size_t tiled_table_bytes(const mmoe_shape& s);
 int planned_tile_rows(const mmoe_shape& s);  // tile height launch_ffn_tiled would use for this shape
 // `inv_perm` null: Yg is indexed by pair id.

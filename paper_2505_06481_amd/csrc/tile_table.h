@@ -56,8 +56,9 @@ inline TileLists tile_lists(int P, int S, int nt_up, int nt_down, int bm)
 
 // One workgroup of 256 threads; every thread of it must call.  `offsets` must be visible to the
 // whole workgroup (written before a workgroup barrier, or by an earlier kernel).
+// Slots that `filt` skips get no tiles.
 __device__ __forceinline__ void build_tile_lists(const int32_t* offsets, int32_t* __restrict__ tab, int S, int nt_up,
-                                                 int nt_down, int bm, TileLists L)
+                                                 int nt_down, int bm, TileLists L, SlotFilter filt = SlotFilter())
 {
     __shared__ int cnt_s[kMaxS];       // rows of each slot
     __shared__ int off_s[kMaxS];       // first row of each slot
@@ -69,7 +70,7 @@ __device__ __forceinline__ void build_tile_lists(const int32_t* offsets, int32_t
     for (int s = tid; s < S; s += 256) {
         const int o = offsets[s];
         off_s[s] = o;
-        cnt_s[s] = offsets[s + 1] - o;
+        cnt_s[s] = filt.skips(s) ? 0 : offsets[s + 1] - o;
     }
     __syncthreads();
     // exclusive prefix sum of the row tiles per slot: a run of slots per thread, then a scan of the runs

@@ -28,7 +28,7 @@ _TORCH_DT = {F32: torch.float32, BF16: torch.bfloat16}
 EXPORTS = [
     "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
     "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_layer_forward_events",
-    "mmoe_layer_forward_static", "mmoe_loader_workspace_bytes", "mmoe_expert_distance", "mmoe_build_expert_map",
+    "mmoe_layer_forward_static", "mmoe_layer_forward_paged", "mmoe_loader_workspace_bytes", "mmoe_expert_distance", "mmoe_build_expert_map",
     "mmoe_validate_inputs", "mmoe_probe_ceilings", "mmoe_expert_plan",
 ]
 
@@ -91,6 +91,7 @@ def lib():
         L.mmoe_layer_forward.argtypes = [sp] + [vp] * 10 + [sz, vp]
         L.mmoe_layer_forward_events.argtypes = [sp] + [vp] * 10 + [sz, vp, vp]
         L.mmoe_layer_forward_static.argtypes = [sp] + [vp] * 10
+        L.mmoe_layer_forward_paged.argtypes = [sp] + [vp] * 14 + [sz, vp, vp, vp]
         L.mmoe_validate_inputs.argtypes = [sp, vp, vp, vp, sz, vp]
         lp = ctypes.POINTER(LoaderShape)
         L.mmoe_loader_workspace_bytes.restype = sz
@@ -307,3 +308,41 @@ def build_expert_map(shape: LoaderShape, distance):
                                        _ptr(rank), _ptr(owner), _ptr(M), _ptr(S), _ptr(src), _stream()),
            "mmoe_build_expert_map")
     return rank, owner, M, S, src
+
+
+def layer_forward_paged(shape: Shape, X, vid, Wr, br, M, W1p, W3p, W2p, resident, host_pool, ws, copy_stream,
+                        Y=None):
+    """The layer with part of the pool in pinned host memory (the paper's miss path).
+    ``resident``: sequence of S flags; ``host_pool``: (hW1p, hW3p, hW2p), each a list of S pinned CPU
+    tensors (one packed slot each) or None for resident slots; ``copy_stream``: a torch.cuda.Stream.
+    Returns (Y, fetched flags as a list)."""
+    dt = _TORCH_DT[shape.dtype]
+    S, d, f = shape.S, shape.d_model, shape.d_ff
+    if Y is None:
+        Y = torch.empty((shape.T, d), dtype=dt, device=X.device)
+    res = (ctypes.c_uint8 * S)(*[1 if r else 0 for r in resident])
+    fetched = (ctypes.c_uint8 * S)()
+
+    def host_ptrs(lst):
+        if lst is None:
+            return None
+        arr = (ctypes.c_void_p * S)()
+        for s in range(S):
+            t = lst[s]
+            if t is not None:
+                if t.is_cuda or not t.is_pinned() or not t.is_contiguous() or t.dtype != dt or t.numel() != d * f:
+                    raise ValueError(f"host slot {s}: needs a pinned, contiguous CPU tensor of {d * f} {dt} elements")
+                arr[s] = t.data_ptr()
+        return arr
+
+    h1, h3, h2 = (host_ptrs(l) for l in host_pool)
+    rc = lib().mmoe_layer_forward_paged(ctypes.byref(shape), _ptr(X, dt, shape.T * d, "X"),
+                                        _ptr(vid, torch.int32, shape.T, "vid"), _ptr(Wr, dt, shape.V * shape.E * d, "Wr"),
+                                        _ptr(br, torch.float32, shape.V * shape.E, "br"),
+                                        _ptr(M, torch.int32, shape.V * shape.E, "M"), _ptr(W1p, dt, S * d * f, "W1p"),
+                                        _ptr(W3p, dt, S * d * f, "W3p"), _ptr(W2p, dt, S * d * f, "W2p"), res, h1, h3, h2,
+                                        _ptr(Y, dt, shape.T * d, "Y"), _ptr(ws, torch.uint8, None, "ws"), ws.numel(),
+                                        _stream(), copy_stream.cuda_stream, fetched)
+    if rc < 0:
+        raise MmoeError(rc, "mmoe_layer_forward_paged")
+    return Y, [int(x) for x in fetched]

@@ -90,6 +90,28 @@ def test_bad_arguments_become_error_codes(mm):
     assert mm.strerror(-99) == "unknown status"
 
 
+def test_paged_layer_argument_checks(mm):
+    L = mm.lib()
+    p = ctypes.c_void_p(4096)
+    q = ctypes.c_void_p(8192)
+    sh = mm.make_shape(4, 256, 256, 1, 2, 2, 1, "f32", "relu")
+    res = (ctypes.c_uint8 * 2)(1, 0)
+    hp = (ctypes.c_void_p * 2)(None, 4096)
+    none_hp = (ctypes.c_void_p * 2)(None, None)
+    big = ctypes.c_size_t(1 << 30)
+
+    def call(resident=res, h1=hp, h2=hp, h3=None, W3=None, stream=p, copy=q, ws=p, ws_bytes=big):
+        return L.mmoe_layer_forward_paged(ctypes.byref(sh), p, p, p, None, p, p, W3, p, resident, h1, h3, h2, p, ws,
+                                          ws_bytes, stream, copy, None)
+
+    assert call(resident=None) == -1
+    assert call(h1=none_hp) == -1                      # a non-resident slot without a host copy
+    assert call(copy=p) == -1                          # the copies need a stream of their own
+    assert call(copy=None) == -1
+    assert call(W3=p) == -5                            # RELU takes no W3
+    assert call(ws_bytes=ctypes.c_size_t(8)) == -6
+
+
 def test_expert_map_builder_argument_checks(mm):
     L = mm.lib()
     p = ctypes.c_void_p(4096)
