@@ -35,7 +35,7 @@ namespace mmoe {
 
 enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2, kTModeGeluH = 3 };
 
-constexpr int kBN = 256;  // weight rows per tile
+constexpr int kBN = 256;  // weight rows per tile: four wavefronts of two 32-row blocks (128 with one block each)
 constexpr int kBK = 64;
 constexpr int kStagesA = 4;    // LDS ring of token tiles
 
@@ -56,10 +56,10 @@ __global__ __launch_bounds__(256) void tile_table_kernel(const int32_t* __restri
     build_tile_lists(offsets, tab, S, nt_up, nt_down, bm, L, filt);
 }
 
-template <int MODE, int BM>
+template <int MODE, int BM, int NB>
 __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const uint16_t* __restrict__ A,
                                                        const int32_t* __restrict__ perm, int kdiv,
-                                                            const int32_t* __restrict__ tab, int list_hi,
+                                                            const int32_t* __restrict__ tab, int hdr, int list_hi,
                                                             int list_lo, const uint16_t* __restrict__ W0,
                                                             const uint16_t* __restrict__ W1,
                                                             void* __restrict__ out, int K, int N, int NT)
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
     const int nt_x = (NT - xcd + kXcds - 1) / kXcds;  // feature tiles owned by this XCD
     const int4* list = reinterpret_cast<const int4*>(tab) + (nt_x == (NT + kXcds - 1) / kXcds ? list_hi : list_lo);
-    const int total_m = tab[0];
+    const int total_m = tab[hdr];
     const int4 ent = list[local];                     // in bounds for every workgroup of the grid
     if (local >= total_m * nt_x) return;              // uniform over the workgroup
     const int s = ent.x;
@@ -83,15 +83,18 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
     const int r0 = ent.z;                             // first row of the tile
     const int cnt = ent.w;                            // rows of the tile that exist (1..256)
 
-    constexpr int kFeat = MODE == kTModeSwigluH ? kBN / 2 : kBN;  // output features per tile
+    // NB = 32-row weight blocks per wavefront: 2 (256 weight rows per tile), or 1 (128: twice as many
+    // tiles for a product that would otherwise leave compute units without work; not for the gated
+    // product, whose wavefronts pair a gate block with an up block)
+    static_assert(NB == 2 || (NB == 1 && MODE != kTModeSwigluH), "weight blocks per wavefront");
+    constexpr int kFeat = MODE == kTModeSwigluH ? kBN / 2 : 128 * NB;  // output features per tile
     const int n0 = nt * kFeat;
 
-    constexpr int NB = 2;             // 32-row weight blocks per wavefront
     constexpr int kWaves = 4;         // one per SIMD
     constexpr int kThreads = kWaves * 64;
     constexpr int kNJ = BM / 32;      // 32-row token sub-tiles per wavefront (all rows of the tile)
     // 16-k slices between a weight fragment's load and its use: what the registers allow
-    constexpr int kBAhead = BM == kBMBig ? 16 : 8;
+    constexpr int kBAhead = (BM == kBMBig || NB == 1) ? 16 : 8;
     constexpr int kNP = BM * 8 / kThreads;  // 16-byte pieces of a token tile per thread
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -143,7 +146,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const uint16_t* w = (MODE == kTModeSwigluH && i == 1) ? W1 : W0;
-        const int nb = MODE == kTModeSwigluH ? (n0 + wn * 32) / 32 : (n0 + wn * 64 + i * 32) / 32;
+        const int nb = MODE == kTModeSwigluH ? (n0 + wn * 32) / 32 : (n0 + wn * (32 * NB) + i * 32) / 32;
         wb[i] = reinterpret_cast<const char*>(w) + ((size_t)s * (N / 32) + nb) * frag_bytes_per_block + lane * 16;
     }
 
@@ -280,13 +283,15 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
                     for (int j = NH; j < NJ; ++j) asm volatile("" ::"v"(fa[j]));
                     // This wavefront's copies of step t+2 were issued two steps ago, after the barrier of
                     // step t-2 (for t < 2: in the prologue); since then it has issued the kNP copies of
-                    // step t+3 and, in the order written here, 16 weight-fragment loads (2 in the rest of
-                    // that slice, 8 in step t-1, 6 in this step): vmcnt(16) leaves the copies of step t+2
-                    // landed, and after the barrier every wavefront may read that step, whose first
+                    // step t+3 and, in the order written here, 8*NB weight-fragment loads (NB in the rest
+                    // of that slice, 4*NB in step t-1, 3*NB in this step): a wait that leaves at most
+                    // kWaitN = min(16, kNP + 8*NB - 4) instructions outstanding leaves the copies of step
+                    // t+2 landed, and after the barrier every wavefront may read that step, whose first
                     // fragments are fetched before the next barrier.
-                    static_assert(kNP + 8 * NB >= 16, "steady state: loads issued after a copy group");
-                    static_assert(kNP + NB * kBAhead + 3 * NB >= 16, "first step: after the copies of step 2");
-                    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+                    constexpr int kWaitN = kNP + 8 * NB - 4 < 16 ? kNP + 8 * NB - 4 : 16;
+                    static_assert(kWaitN >= kNP, "the copies of step t+3 stay in flight");
+                    static_assert(kNP + NB * kBAhead + 3 * NB >= kWaitN, "first step: after the copies of step 2");
+                    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kWaitN) : "memory");
                     copy_a(st, min(t + 4, last));  // tokens of step t+4; past the end: a harmless reload
 #pragma unroll
                     for (int j = NH; j < NJ; ++j) mma_roll(j, fb, next);
@@ -328,7 +333,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
     constexpr int kLpr = kRowB / 16;                  // lanes that read one row back
     constexpr int kRpi = 64 / kLpr;                   // rows per read-back instruction
     constexpr int kChunks = MODE == kTModeSwigluH ? 1 : NB;       // 32-feature chunks this wavefront stores
-    const int wfeat = MODE == kTModeSwigluH ? wn * 32 : wn * 64;
+    const int wfeat = MODE == kTModeSwigluH ? wn * 32 : wn * (32 * NB);
     // the patches reuse the token ring: every wavefront has left the main loop
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     char* ebuf = lds_a + wave * (32 * (32 * 4 + 16));
@@ -364,7 +369,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
             float o[16];
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                if (MODE == kTModeSwigluH) o[e] = silu_mul_t(acc[j][0][e], acc[j][1][e]);
+                if (MODE == kTModeSwigluH) o[e] = silu_mul_t(acc[j][0][e], acc[j][NB - 1][e]);
                 else if (MODE == kTModeReluH) o[e] = fmaxf(acc[j][c][e], 0.0f);
                 else if (MODE == kTModeGeluH) o[e] = 0.5f * acc[j][c][e] * (1.0f + erff(acc[j][c][e] * 0.70710678118654752440f));
                 else o[e] = acc[j][c][e];
@@ -374,10 +379,23 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
     }
 }
 
-static void tiled_nts(const mmoe_shape& s, int& nt_up, int& nt_down)
+// Weight blocks per wavefront of a product with N output features: 2, or 1 (tiles of 128 weight
+// rows, twice as many of them) when 128-row token tiles are in use and the product would otherwise
+// have fewer tiles than the chip holds workgroups at a time.  Shape only.
+constexpr int kNb1Room = 512;  // two workgroups of 128-row tiles on each of 256 compute units
+static int planned_nb(const mmoe_shape& s, int bm, int N, bool gated)
 {
-    nt_up = s.act == MMOE_SWIGLU ? s.d_ff / (kBN / 2) : s.d_ff / kBN;
-    nt_down = s.d_model / kBN;
+    if (gated || bm != kBMSmall) return 2;
+    const int64_t P = (int64_t)s.T * s.top_k;
+    return ((P + bm - 1) / bm) * (N / kBN) < kNb1Room ? 1 : 2;
+}
+
+static void tiled_nts(const mmoe_shape& s, int bm, int& nt_up, int& nt_down, int& nb_up, int& nb_down)
+{
+    nb_up = planned_nb(s, bm, s.d_ff, s.act == MMOE_SWIGLU);
+    nb_down = planned_nb(s, bm, s.d_model, false);
+    nt_up = s.act == MMOE_SWIGLU ? s.d_ff / (kBN / 2) : s.d_ff / (128 * nb_up);
+    nt_down = s.d_model / (128 * nb_down);
 }
 
 // Tile height: 128 rows (two workgroups per compute unit, so one's prologue and epilogue hide
@@ -394,47 +412,64 @@ int planned_tile_rows(const mmoe_shape& s)
     return (s.d_model <= 1024 || P < (int64_t)64 * s.S) ? kBMSmall : kBMBig;
 }
 
-size_t tiled_table_bytes(const mmoe_shape& s)
+// Most sub-tiles of a row tile: a full tile.  (Shorter tiles for products with few tiles were
+// measured on the Switch shape and lose: every tile streams its whole weight panel, and a step of
+// a short tile is over before the copies issued two steps earlier have landed.)
+static int planned_upt(const mmoe_shape&, int bm, int) { return bm / 32; }
+
+// Everything the launches of one shape share: tile height, weight blocks per wavefront and feature
+// tiles of both products, and the tile lists' layout.
+struct TiledPlan {
+    int bm, nt_up, nt_down, nb_up, nb_down;
+    TileLists L;
+};
+
+static TiledPlan tiled_plan(const mmoe_shape& s)
 {
-    int nt_up, nt_down;
-    tiled_nts(s, nt_up, nt_down);
-    return align256(tile_lists(s.T * s.top_k, s.S, nt_up, nt_down, kBMSmall).bytes);  // the larger of the two
+    TiledPlan p;
+    p.bm = planned_tile_rows(s);
+    tiled_nts(s, p.bm, p.nt_up, p.nt_down, p.nb_up, p.nb_down);
+    p.L = tile_lists(s.T * s.top_k, s.S, p.nt_up, p.nt_down, planned_upt(s, p.bm, p.nt_up),
+                     planned_upt(s, p.bm, p.nt_down));
+    return p;
 }
 
-template <int BM>
-static void launch_tiled_products(const mmoe_shape& s, const TileLists& L, const void* rows, const int32_t* perm,
-                                  const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg,
-                                  const int32_t* tab, int nt_up, int nt_down, hipStream_t st, hipEvent_t mid,
-                                  bool& event_failed)
+size_t tiled_table_bytes(const mmoe_shape& s)
 {
-    const int d = s.d_model, f = s.d_ff;
-    dim3 block(256);
-    const uint16_t* nul = nullptr;
-    if (s.act == MMOE_SWIGLU)
-        hipLaunchKernelGGL((tiled_kernel<kTModeSwigluH, BM>), dim3(L.cap[0] * kXcds), block, 0, st,
-                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
-                           (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, nt_up);
-    else if (s.act == MMOE_GELU)
-        hipLaunchKernelGGL((tiled_kernel<kTModeGeluH, BM>), dim3(L.cap[0] * kXcds), block, 0, st,
-                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
-                           (const uint16_t*)W1p, nul, H, d, f, nt_up);
-    else
-        hipLaunchKernelGGL((tiled_kernel<kTModeReluH, BM>), dim3(L.cap[0] * kXcds), block, 0, st,
-                           (const uint16_t*)rows, perm, s.top_k, tab, L.list[0][0], L.list[0][1],
-                           (const uint16_t*)W1p, nul, H, d, f, nt_up);
-    if (mid && hipEventRecord(mid, st) != hipSuccess) event_failed = true;
-    hipLaunchKernelGGL((tiled_kernel<kTModePlainF32, BM>), dim3(L.cap[1] * kXcds), block, 0, st,
-                       (const uint16_t*)H, (const int32_t*)nullptr, 1, tab, L.list[1][0], L.list[1][1],
-                       (const uint16_t*)W2p, nul, (void*)Yg, f, d, nt_down);
+    // the most entries any plan of this shape can have: the shortest tiles, the narrowest feature tiles
+    const int nt_up = s.act == MMOE_SWIGLU ? s.d_ff / (kBN / 2) : s.d_ff / 128;
+    return align256(tile_lists(s.T * s.top_k, s.S, nt_up, s.d_model / 128, 1, 1).bytes);
+}
+
+template <int MODE, int BM, int NB>
+static void launch_product(const TiledPlan& p, int prod, const void* A, const int32_t* perm, int kdiv, const int32_t* tab,
+                           const void* W0, const void* W1, void* out, int K, int N, hipStream_t st)
+{
+    hipLaunchKernelGGL((tiled_kernel<MODE, BM, NB>), dim3(p.L.cap[prod] * kXcds), dim3(256), 0, st, (const uint16_t*)A,
+                       perm, kdiv, tab, p.L.hdr + prod, p.L.list[prod][0], p.L.list[prod][1], (const uint16_t*)W0,
+                       (const uint16_t*)W1, out, K, N, prod == 0 ? p.nt_up : p.nt_down);
+}
+
+// one weight block per wavefront exists for 128-row tiles only (planned_nb)
+template <int MODE>
+static void launch_plain_product(const TiledPlan& p, int prod, const void* A, const int32_t* perm, int kdiv,
+                                 const int32_t* tab, const void* W0, void* out, int K, int N, hipStream_t st)
+{
+    const int nb = prod == 0 ? p.nb_up : p.nb_down;
+    if (p.bm == kBMBig) launch_product<MODE, kBMBig, 2>(p, prod, A, perm, kdiv, tab, W0, nullptr, out, K, N, st);
+    else if (nb == 2) launch_product<MODE, kBMSmall, 2>(p, prod, A, perm, kdiv, tab, W0, nullptr, out, K, N, st);
+    else launch_product<MODE, kBMSmall, 1>(p, prod, A, perm, kdiv, tab, W0, nullptr, out, K, N, st);
 }
 
 TileJob tile_job(const mmoe_shape& s, int32_t* tab)
 {
+    const TiledPlan p = tiled_plan(s);
     TileJob j;
     j.tab = tab;
-    tiled_nts(s, j.nt_up, j.nt_down);
-    j.bm = planned_tile_rows(s);
-    j.L = tile_lists(s.T * s.top_k, s.S, j.nt_up, j.nt_down, j.bm);
+    j.nt_up = p.nt_up;
+    j.nt_down = p.nt_down;
+    j.bm = p.bm;
+    j.L = p.L;
     return j;
 }
 
@@ -445,21 +480,22 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
     if (s.dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     const int P = s.T * s.top_k, d = s.d_model, f = s.d_ff;
     if ((int64_t)P * (d > f ? d : f) >= ((int64_t)1 << 31)) return MMOE_ERR_LIMIT;  // 32-bit byte offsets inside a panel
-    int nt_up, nt_down;
-    tiled_nts(s, nt_up, nt_down);
-    const int bm = planned_tile_rows(s);
-    const TileLists L = tile_lists(P, s.S, nt_up, nt_down, bm);
+    const TiledPlan p = tiled_plan(s);
     if (!tab_ready)
-        hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, nt_up, nt_down, bm, L,
+        hipLaunchKernelGGL(tile_table_kernel, dim3(1), dim3(256), 0, st, offsets, tab, s.S, p.nt_up, p.nt_down, p.bm, p.L,
                            filt);
-    bool event_failed = false;
-    if (bm == kBMBig)
-        launch_tiled_products<kBMBig>(s, L, rows, perm, W1p, W3p, W2p, H, Yg, tab, nt_up, nt_down, st, mid,
-                                      event_failed);
-    else
-        launch_tiled_products<kBMSmall>(s, L, rows, perm, W1p, W3p, W2p, H, Yg, tab, nt_up, nt_down, st, mid,
-                                        event_failed);
-    if (event_failed) return MMOE_ERR_LAUNCH;
+    if (s.act == MMOE_SWIGLU) {
+        if (p.bm == kBMBig)
+            launch_product<kTModeSwigluH, kBMBig, 2>(p, 0, rows, perm, s.top_k, tab, W1p, W3p, H, d, f, st);
+        else
+            launch_product<kTModeSwigluH, kBMSmall, 2>(p, 0, rows, perm, s.top_k, tab, W1p, W3p, H, d, f, st);
+    } else if (s.act == MMOE_GELU) {
+        launch_plain_product<kTModeGeluH>(p, 0, rows, perm, s.top_k, tab, W1p, H, d, f, st);
+    } else {
+        launch_plain_product<kTModeReluH>(p, 0, rows, perm, s.top_k, tab, W1p, H, d, f, st);
+    }
+    if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
+    launch_plain_product<kTModePlainF32>(p, 1, H, nullptr, 1, tab, W2p, Yg, f, d, st);
     return launch_status();
 }
 

@@ -15,13 +15,13 @@ constexpr int kNtGroup = 4;  // least number of feature tiles whose workgroups s
 // Tile lists, written by one workgroup from the device-side `offsets`.
 //
 // Row tiles.  A slot with c rows is u = ceil(c / 32) sub-tiles of 32 rows.  It is cut into
-// mt = ceil(u / upt) tiles (upt = sub-tiles of a full tile: 8 or 4) whose heights differ by at
-// most one sub-tile: the first u mod mt tiles have floor(u / mt) + 1 sub-tiles, the others
+// mt = ceil(u / upt) tiles whose heights differ by at most one sub-tile (upt = most sub-tiles of a
+// tile, given per product by the host: a full tile's 8 or 4): the first u mod mt tiles have floor(u / mt) + 1 sub-tiles, the others
 // floor(u / mt).  No slot has a short last tile (a tile of one sub-tile streams its weight panel
 // for an eighth of the arithmetic), and no matrix instruction is spent on padding beyond the last
 // partial sub-tile.
 //
-// Order.  tab[0] = number of row tiles; four lists of int4 entries {slot, feature tile within
+// Order.  tab[0], tab[1] = number of row tiles of the up and of the down product; four lists of int4 entries {slot, feature tile within
 // the XCD, first row, rows}, one per (product, feature tiles per XCD): a product with NT feature
 // tiles gives XCD x the tiles nt with nt mod 8 == x, that is ceil or floor of NT/8 of them; list
 // entry `local` is the tile that the workgroup with id 8*local + x computes.  Entries are listed
@@ -34,16 +34,19 @@ struct TileLists {
     int hdr;        // int32 index of tab[0]
     int list[2][2]; // [product: up, down][0: ceil(NT/8) per XCD, 1: floor] -> int4 index into tab
     int cap[2];     // entries reserved per list of each product
+    int upt[2];     // most 32-row sub-tiles of a row tile, per product
     size_t bytes;
 };
 
-inline TileLists tile_lists(int P, int S, int nt_up, int nt_down, int bm)
+inline TileLists tile_lists(int P, int S, int nt_up, int nt_down, int upt_up, int upt_down)
 {
     TileLists L;
-    const int mt = (P + bm - 1) / bm + S;  // upper bound of the number of row tiles
     L.hdr = 0;
-    L.cap[0] = mt * ((nt_up + kXcds - 1) / kXcds);
-    L.cap[1] = mt * ((nt_down + kXcds - 1) / kXcds);
+    L.upt[0] = upt_up;
+    L.upt[1] = upt_down;
+    // upper bound of the number of row tiles: sum_s ceil(ceil(c_s / 32) / upt) <= P / (32 upt) + S
+    L.cap[0] = ((P + 32 * upt_up - 1) / (32 * upt_up) + S) * ((nt_up + kXcds - 1) / kXcds);
+    L.cap[1] = ((P + 32 * upt_down - 1) / (32 * upt_down) + S) * ((nt_down + kXcds - 1) / kXcds);
     int at = 16;  // int4 units; the header takes the first 256 bytes
     for (int p = 0; p < 2; ++p)
         for (int c = 0; c < 2; ++c) {
@@ -65,7 +68,6 @@ __device__ __forceinline__ void build_tile_lists(const int32_t* offsets, int32_t
     __shared__ int base[kMaxS + 1];    // row tiles of the slots before each slot
     __shared__ int part[256];
     const int tid = threadIdx.x;
-    const int upt = bm / 32;                   // sub-tiles of a full tile
     const int conc = bm == kBMBig ? 32 : 64;   // workgroups resident on one XCD
     for (int s = tid; s < S; s += 256) {
         const int o = offsets[s];
@@ -73,34 +75,36 @@ __device__ __forceinline__ void build_tile_lists(const int32_t* offsets, int32_t
         cnt_s[s] = filt.skips(s) ? 0 : offsets[s + 1] - o;
     }
     __syncthreads();
-    // exclusive prefix sum of the row tiles per slot: a run of slots per thread, then a scan of the runs
-    auto tiles_of = [&](int s) { return (((cnt_s[s] + 31) >> 5) + upt - 1) / upt; };
-    const int chunk = (S + 255) / 256;
-    const int s_lo = min(tid * chunk, S), s_hi = min(s_lo + chunk, S);
-    int mine = 0;
-    for (int s = s_lo; s < s_hi; ++s) mine += tiles_of(s);
-    part[tid] = mine;
-    __syncthreads();
-    for (int dlt = 1; dlt < 256; dlt <<= 1) {
-        const int add = tid >= dlt ? part[tid - dlt] : 0;
-        __syncthreads();
-        part[tid] += add;
-        __syncthreads();
-    }
-    int run = part[tid] - mine;
-    for (int s = s_lo; s < s_hi; ++s) {
-        base[s] = run;
-        run += tiles_of(s);
-    }
-    const int total_m = part[255];
-    if (tid == 0) {
-        base[S] = total_m;
-        tab[L.hdr] = total_m;
-    }
-    __syncthreads();
     int4* lists = reinterpret_cast<int4*>(tab);
     for (int p = 0; p < 2; ++p) {
         const int NT = p == 0 ? nt_up : nt_down;
+        const int upt = L.upt[p];
+        // exclusive prefix sum of the row tiles per slot: a run of slots per thread, then a scan of the runs
+        auto tiles_of = [&](int s) { return (((cnt_s[s] + 31) >> 5) + upt - 1) / upt; };
+        const int chunk = (S + 255) / 256;
+        const int s_lo = min(tid * chunk, S), s_hi = min(s_lo + chunk, S);
+        int mine = 0;
+        for (int s = s_lo; s < s_hi; ++s) mine += tiles_of(s);
+        __syncthreads();  // the lists of the product before have been written: base and part are free
+        part[tid] = mine;
+        __syncthreads();
+        for (int dlt = 1; dlt < 256; dlt <<= 1) {
+            const int add = tid >= dlt ? part[tid - dlt] : 0;
+            __syncthreads();
+            part[tid] += add;
+            __syncthreads();
+        }
+        int run = part[tid] - mine;
+        for (int s = s_lo; s < s_hi; ++s) {
+            base[s] = run;
+            run += tiles_of(s);
+        }
+        const int total_m = part[255];
+        if (tid == 0) {
+            base[S] = total_m;
+            tab[L.hdr + p] = total_m;
+        }
+        __syncthreads();
         for (int c = 0; c < 2; ++c) {
             if (c == 1 && NT % kXcds == 0) break;  // every XCD has the same number of feature tiles: one list
             const int nt_x = c == 0 ? (NT + kXcds - 1) / kXcds : NT / kXcds;

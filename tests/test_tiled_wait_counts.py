@@ -168,11 +168,13 @@ def test_checker_flags_a_short_window():
 def test_every_written_out_wait_of_the_tiled_kernel_is_covered():
     text = device_assembly()
     fns = functions(text, "_ZN4mmoe12tiled_kernel")
-    assert len(fns) == 8, [f.name for f in fns]          # 4 products (three activations, down) x 2 tile heights
+    # 4 products (three activations, down) x 2 tile heights, and the three products without a gate
+    # once more with one weight block per wavefront (128-row tiles only)
+    assert len(fns) == 11, [f.name for f in fns]
     for fn in fns:
-        bm = int(re.search(r"ILi\d+ELi(\d+)EE", fn.name).group(1))
+        bm, nb = (int(x) for x in re.search(r"ILi\d+ELi(\d+)ELi(\d+)EE", fn.name).groups())
         knp = bm * 8 // 256                               # copies per wavefront and step
-        nj_variants, steps_per_trip = bm // 32 if bm == 256 else 4, (16 if bm == 256 else 8) // 4
+        nj_variants, steps_per_trip = bm // 32 if bm == 256 else 4, (16 if bm == 256 or nb == 1 else 8) // 4
         res = check_function(fn, knp)
         # one wait in the prologue and one per unrolled step of the main loop, per instantiation
         assert len(res) == nj_variants * (1 + steps_per_trip), (fn.name, len(res))
