@@ -32,12 +32,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).  The figures belong
 # to one version of the kernel source; with any other version `traffic` is null.
 TRAFFIC = {
-    "ffn_tiled.hip": {"sha256": "02be35afa1ba2a7c3576abcb2fc02adada79f7bb52efe8ff9face40709e17304",
+    "ffn_tiled.hip": {"sha256": "a266c2cbe0fe93b3fc6bb676b1e3152932c77ddf6da6ed56db0b979da5ee5ffd",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 13700513403, "write_bytes": 469762288},
-    "ffn_skinny.hip": {"sha256": "e3d20992929bfea46d211c6fb4142b0d27beb9985942e3cdf8065493e4fd6502",
+                      "fetch_bytes": 11060124417, "write_bytes": 469762358},
+    "ffn_skinny.hip": {"sha256": "50b460970d089d7c122e7f3ef741fae8eb6cdc5db845ca63ed882d4a717e9ba2",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3067231979, "write_bytes": 3670654},
+                       "fetch_bytes": 3067991223, "write_bytes": 3670613},
 }
 
 
