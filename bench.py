@@ -41,6 +41,10 @@ TRAFFIC = {
 }
 
 
+TRAFFIC_SOURCE = ("recorded from two rocprofv3 --pmc passes (profiles/*counters.txt), not measured in this run; "
+                  "null when the kernel source has changed since")
+
+
 def measured_traffic(source, workload):
     """Counter-derived HBM bytes (read + written) per launch of the up-product kernel, or None
     if the kernel source has changed since the counters were taken."""
@@ -262,7 +266,7 @@ def roofline(cfg, res, skinny):
         alg_bytes = active * nw * d * f * es + P * d * es + P * f * es
         ach = alg_bytes / dur_s / 1e9
         return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
-                    traffic=measured_traffic("ffn_skinny.hip", cfg.name),
+                    traffic=measured_traffic("ffn_skinny.hip", cfg.name), traffic_source=TRAFFIC_SOURCE,
                     kernel=("skinny_frag_kernel" if cfg.dtype == "bf16" else "skinny_kernel") + " (up product)",
                     bytes_per_launch=alg_bytes,
                     avg_launch_ms=dur_s * 1e3)
@@ -270,7 +274,8 @@ def roofline(cfg, res, skinny):
     ach = flops / dur_s / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_MFMA_TFLOPS
     return dict(bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
-                traffic=measured_traffic("ffn_tiled.hip", cfg.name), kernel="tiled_kernel (up product)",
+                traffic=measured_traffic("ffn_tiled.hip", cfg.name), traffic_source=TRAFFIC_SOURCE,
+                kernel="tiled_kernel (up product)",
                 flops_per_launch=flops, avg_launch_ms=dur_s * 1e3)
 
 
