@@ -106,7 +106,12 @@ __device__ __forceinline__ RowSet slot_rows(const int32_t* __restrict__ offsets,
     return rs;
 }
 
-template <typename T, int NW, int KU, int MODE>
+// SPLITK: the four wavefronts split the reduction dimension of one 16-feature block and meet in
+// LDS (long reductions).  !SPLITK: every wavefront owns a 16-feature block of its own and walks the
+// whole reduction dimension (short reductions, where a quarter of K is one or two iterations: all
+// latency, no pipelining): 64 features per workgroup, no LDS reduction, the token rows fetched a
+// quarter as often per weight byte.
+template <typename T, int NW, int KU, int MODE, bool SPLITK>
 __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict__ A,
                                                             const int32_t* __restrict__ perm, int kdiv,
                                                             const int32_t* __restrict__ offsets,
@@ -121,15 +126,17 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
     __shared__ int mine_cnt;
 
     const int s = blockIdx.y;
-    const int n0 = blockIdx.x * 16;
     const RowSet rs = slot_rows(offsets, perm, kdiv, slot_of_pair, P, s, mine, &mine_cnt, filt);
     const int cnt = rs.cnt;
     if (cnt <= 0) return;  // uniform over the workgroup
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
+    const int n0 = SPLITK ? blockIdx.x * 16 : (blockIdx.x * kSkWaves + wave) * 16;
     const int li = lane & 15, g = lane >> 4;
     const int nit = K / (KSS * KU);
+    constexpr int kFirst = SPLITK ? -1 : 0;        // first iteration of a wavefront: its index, or 0
+    constexpr int kStride = SPLITK ? kSkWaves : 1;  // iterations between two of one wavefront
 
     const T* wrow[NW];
     wrow[0] = W0 + ((size_t)s * N + n0 + li) * K + g * (4 * EPB);
@@ -150,7 +157,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
             for (int w = 0; w < NW; ++w) acc[mb][w] = f32x4{0.f, 0.f, 0.f, 0.f};
 
         u32x4 wcur[NW][KU][4], wnxt[NW][KU][4];
-        int it = wave;
+        int it = kFirst < 0 ? wave : kFirst;
         if (it < nit) {
 #pragma unroll
             for (int w = 0; w < NW; ++w)
@@ -161,7 +168,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
                         wcur[w][u][q] =
                             *reinterpret_cast<const u32x4*>(wrow[w] + (size_t)(it * KU + u) * KSS + q * EPB);
         }
-        for (; it < nit; it += kSkWaves) {
+        for (; it < nit; it += kStride) {
             u32x4 xa[kSkMB][KU][4];
 #pragma unroll
             for (int mb = 0; mb < kSkMB; ++mb)
@@ -173,7 +180,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
                             xa[mb][u][q] =
                                 *reinterpret_cast<const u32x4*>(arow[mb] + (size_t)(it * KU + u) * KSS + q * EPB);
                 }
-            const int itn = it + kSkWaves;
+            const int itn = it + kStride;
             if (itn < nit) {  // the next weights: the youngest loads, still in flight during the math below
 #pragma unroll
                 for (int w = 0; w < NW; ++w)
@@ -203,6 +210,41 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
                     for (int q = 0; q < 4; ++q) wcur[w][u][q] = wnxt[w][u][q];
         }
 
+        // accumulator element i of lane l is output feature n0 + 4*(l/16) + i of token column l%16
+        auto finish = [&](int row, int l, const float (&v)[NW][4]) {
+            float o[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (MODE == kModeSwigluH) o[i] = silu_mul(v[0][i], v[NW - 1][i]);
+                else if (MODE == kModeReluH) o[i] = fmaxf(v[0][i], 0.0f);
+                else if (MODE == kModeGeluH) o[i] = gelu(v[0][i]);
+                else o[i] = v[0][i];
+            }
+            const size_t at = (size_t)rs.out_row(row) * N + n0 + 4 * (l >> 4);
+            if (MODE == kModePlainF32 || sizeof(T) == 4) {
+                *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = f32x4{o[0], o[1], o[2], o[3]};
+            } else {
+                u32x2 pk;
+                pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
+                pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
+                *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) = pk;
+            }
+        };
+        if (!SPLITK) {  // every wavefront finishes its own 16 features straight from its accumulators
+#pragma unroll
+            for (int mb = 0; mb < kSkMB; ++mb) {
+                const int row = pass0 + mb * 16 + (lane & 15);
+                if (mb < nmb && row < cnt) {
+                    float v[NW][4];
+#pragma unroll
+                    for (int w = 0; w < NW; ++w)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[w][i] = acc[mb][w][i];
+                    finish(row, lane, v);
+                }
+            }
+            continue;
+        }
 #pragma unroll
         for (int mb = 0; mb < kSkMB; ++mb)
 #pragma unroll
@@ -210,7 +252,6 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
 #pragma unroll
                 for (int i = 0; i < 4; ++i) red[wave][mb][w][lane][i] = acc[mb][w][i];
         __syncthreads();
-        // accumulator element i of lane l is output feature n0 + 4*(l/16) + i of token column l%16
         for (int idx = threadIdx.x; idx < nmb * kWave; idx += kSkThreads) {
             const int mb = idx / kWave, l = idx % kWave;
             const int row = pass0 + mb * 16 + (l & 15);
@@ -221,23 +262,7 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
                         v[w][i] = (red[0][mb][w][l][i] + red[1][mb][w][l][i]) + (red[2][mb][w][l][i] + red[3][mb][w][l][i]);
-                float o[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (MODE == kModeSwigluH) o[i] = silu_mul(v[0][i], v[NW - 1][i]);
-                    else if (MODE == kModeReluH) o[i] = fmaxf(v[0][i], 0.0f);
-                    else if (MODE == kModeGeluH) o[i] = gelu(v[0][i]);
-                    else o[i] = v[0][i];
-                }
-                const size_t at = (size_t)rs.out_row(row) * N + n0 + 4 * (l >> 4);
-                if (MODE == kModePlainF32 || sizeof(T) == 4) {
-                    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = f32x4{o[0], o[1], o[2], o[3]};
-                } else {
-                    u32x2 pk;
-                    pk[0] = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
-                    pk[1] = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
-                    *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(out) + at) = pk;
-                }
+                finish(row, l, v);
             }
         }
         __syncthreads();
@@ -402,28 +427,57 @@ static int run_skinny_bf16(const mmoe_shape& s, const void* rows, const int32_t*
     return launch_status();
 }
 
+template <typename T, bool SPLITK>
+static void launch_skinny_products(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
+                                   const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p,
+                                   void* H, float* Yg, hipStream_t st, hipEvent_t mid, SlotFilter filt, bool up,
+                                   bool down)
+{
+    const int32_t* noperm = nullptr;
+    const int d = s.d_model, f = s.d_ff, P = s.T * s.top_k;
+    constexpr int kFeat = SPLITK ? 16 : 16 * kSkWaves;  // output features per workgroup
+    dim3 block(kSkThreads);
+    dim3 g1(f / kFeat, s.S), g2(d / kFeat, s.S);
+    const T* nul = nullptr;
+    if (up) {
+        if (s.act == MMOE_SWIGLU)
+            hipLaunchKernelGGL((skinny_kernel<T, 2, 1, kModeSwigluH, SPLITK>), g1, block, 0, st, (const T*)rows, perm,
+                               s.top_k, offsets, slot_of_pair, P, (const T*)W1p, (const T*)W3p, H, d, f, filt);
+        else if (s.act == MMOE_GELU)
+            hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeGeluH, SPLITK>), g1, block, 0, st, (const T*)rows, perm,
+                               s.top_k, offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt);
+        else
+            hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH, SPLITK>), g1, block, 0, st, (const T*)rows, perm,
+                               s.top_k, offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt);
+    }
+    if (down)
+        hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModePlainF32, SPLITK>), g2, block, 0, st, (const T*)H, noperm, 1,
+                           offsets, slot_of_pair, P, (const T*)W2p, nul, (void*)Yg, f, d, filt);
+    (void)mid;
+}
+
+// A product whose reduction dimension gives a wavefront fewer than three iterations when split four
+// ways keeps it whole (K <= 1024 for fp32).
+static bool whole_k(int K) { return K <= 1024; }
+
 template <typename T>
 static int run_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                       const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg,
                       hipStream_t st, hipEvent_t mid, SlotFilter filt)
 {
-    const int32_t* noperm = nullptr;
-    const int d = s.d_model, f = s.d_ff, P = s.T * s.top_k;
-    dim3 block(kSkThreads);
-    dim3 g1(f / 16, s.S), g2(d / 16, s.S);
-    const T* nul = nullptr;
-    if (s.act == MMOE_SWIGLU)
-        hipLaunchKernelGGL((skinny_kernel<T, 2, 1, kModeSwigluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
-                           offsets, slot_of_pair, P, (const T*)W1p, (const T*)W3p, H, d, f, filt);
-    else if (s.act == MMOE_GELU)
-        hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeGeluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
-                           offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt);
+    if (whole_k(s.d_model))
+        launch_skinny_products<T, false>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, true,
+                                         false);
     else
-        hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH>), g1, block, 0, st, (const T*)rows, perm, s.top_k,
-                           offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt);
+        launch_skinny_products<T, true>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, true,
+                                        false);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModePlainF32>), g2, block, 0, st, (const T*)H, noperm, 1,
-                       offsets, slot_of_pair, P, (const T*)W2p, nul, (void*)Yg, f, d, filt);
+    if (whole_k(s.d_ff))
+        launch_skinny_products<T, false>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, false,
+                                         true);
+    else
+        launch_skinny_products<T, true>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, false,
+                                        true);
     return launch_status();
 }
 
