@@ -333,6 +333,17 @@ int mmoe_build_expert_map(const mmoe_loader_shape *shape, const double *distance
                           int32_t *owner, int32_t *M, int32_t *S, int32_t *slot_src, void *stream);
 
 /*
+ * The loader's last step for one layer: the consolidated pool itself ("load M[idx].expert[iL][iE] to
+ * GPU", Algorithm 1).  With the variants already in device memory the load is a device copy:
+ * pool[m][s] (HOST array of n_mats DEVICE pointers, each [n_slots, mat_elems[m]] in the plain
+ * layout) = matrix m of the (variant, expert) that slot_src names for slot s of `layer`.
+ * slot_src is the whole [L, V*E, 2] array written by mmoe_build_expert_map (DEVICE); n_slots = S[layer]
+ * (the caller reads S back to size the pool).  Follow with mmoe_pack_weights.
+ */
+int mmoe_assemble_pool(const mmoe_loader_shape *shape, const void *const *mats, const int32_t *slot_src,
+                       int32_t layer, int32_t n_slots, void *const *pool, void *stream);
+
+/*
  * Debugging aid, SYNCHRONISES the stream: checks on the device that every vid[t] is in
  * [0,V) and every M[v][e] in [0,S).  Returns 0 if so, 1 if not, a negative status on
  * argument errors.  `ws` needs 256 bytes.

@@ -444,6 +444,24 @@ int mmoe_build_expert_map(const mmoe_loader_shape* shape, const double* distance
     return launch_expert_map(*shape, distance, rank, owner, M, S, slot_src, (hipStream_t)stream);
 }
 
+int mmoe_assemble_pool(const mmoe_loader_shape* shape, const void* const* mats, const int32_t* slot_src, int32_t layer,
+                       int32_t n_slots, void* const* pool, void* stream)
+{
+    int rc = check_loader_shape(shape);
+    if (rc) return rc;
+    if (!mats || !slot_src || !pool) return MMOE_ERR_NULL;
+    if (layer < 0 || layer >= shape->L || n_slots <= 0 || n_slots > shape->V * shape->E) return MMOE_ERR_DIM;
+    for (int i = 0; i < shape->V * shape->n_mats; ++i)
+        if (!mats[i]) return MMOE_ERR_NULL;
+    for (int m = 0; m < shape->n_mats; ++m) {
+        if (!pool[m]) return MMOE_ERR_NULL;
+        if (misaligned(pool[m], 16)) return MMOE_ERR_ALIGN;
+    }
+    if (misaligned(slot_src, 4)) return MMOE_ERR_ALIGN;
+    return launch_assemble_pool(*shape, mats, slot_src + (size_t)layer * shape->V * shape->E * 2, layer, n_slots, pool,
+                                (hipStream_t)stream);
+}
+
 int mmoe_validate_inputs(const mmoe_shape* shape, const int32_t* vid, const int32_t* M, void* ws,
                          size_t ws_bytes, void* stream)
 {

@@ -101,6 +101,8 @@ int launch_validate(const mmoe_shape& s, const int32_t* vid, const int32_t* M, i
 size_t loader_ws_bytes(const mmoe_loader_shape& s);
 int launch_expert_distance(const mmoe_loader_shape& s, const void* const* mats, double* distance, double* partial,
                            hipStream_t st);
+int launch_assemble_pool(const mmoe_loader_shape& s, const void* const* mats, const int32_t* slot_src_layer, int layer,
+                         int n_slots, void* const* pool, hipStream_t st);
 int launch_expert_map(const mmoe_loader_shape& s, const double* distance, int32_t* rank, int32_t* owner, int32_t* M,
                       int32_t* S, int32_t* slot_src, hipStream_t st);
 

@@ -188,6 +188,44 @@ __global__ __launch_bounds__(kTabThreads) void expert_map_kernel(const double* _
     }
 }
 
+// Pool of one layer from the table: slot s of matrix m is a copy of the (variant, expert) that
+// slot_src names ("load M[idx].expert[iL][iE] to GPU", Algorithm 1; here the variants already are in
+// device memory, so the load is a device copy).  grid (chunks, S_l, n_mats), 16 bytes per lane and step.
+__global__ __launch_bounds__(kTabThreads) void assemble_pool_kernel(LoaderPtrs ptrs, const int32_t* __restrict__ slot_src,
+                                                                   int layer, int E, int64_t p0, int64_t p1, int64_t p2,
+                                                                   u32x4* __restrict__ d0, u32x4* __restrict__ d1,
+                                                                   u32x4* __restrict__ d2)
+{
+    const int s = blockIdx.y, m = blockIdx.z;
+    const int v = slot_src[2 * s], e = slot_src[2 * s + 1];
+    if (v < 0) return;  // uniform over the workgroup: a row past the layer's last slot
+    const int64_t pieces = m == 0 ? p0 : (m == 1 ? p1 : p2);
+    u32x4* dst = (m == 0 ? d0 : (m == 1 ? d1 : d2)) + (int64_t)s * pieces;
+    const u32x4* src = reinterpret_cast<const u32x4*>(ptrs.mat[v][m]) + ((int64_t)layer * E + e) * pieces;
+    for (int64_t q = (int64_t)blockIdx.x * kTabThreads + threadIdx.x; q < pieces; q += (int64_t)gridDim.x * kTabThreads)
+        dst[q] = src[q];
+}
+
+int launch_assemble_pool(const mmoe_loader_shape& s, const void* const* mats, const int32_t* slot_src_layer, int layer,
+                         int n_slots, void* const* pool, hipStream_t st)
+{
+    LoaderPtrs p = {};
+    for (int v = 0; v < s.V; ++v)
+        for (int m = 0; m < s.n_mats; ++m) p.mat[v][m] = mats[v * s.n_mats + m];
+    const int el = s.dtype == MMOE_BF16 ? 8 : 4;
+    int64_t pc[3] = {0, 0, 0};
+    int64_t most = 0;
+    for (int m = 0; m < s.n_mats; ++m) {
+        pc[m] = s.mat_elems[m] / el;
+        most = pc[m] > most ? pc[m] : most;
+    }
+    const int chunks = (int)((most + (int64_t)kTabThreads * 8 - 1) / ((int64_t)kTabThreads * 8));  // 8 pieces per thread
+    hipLaunchKernelGGL(assemble_pool_kernel, dim3(chunks > 65535 ? 65535 : chunks, n_slots, s.n_mats), dim3(kTabThreads),
+                       0, st, p, slot_src_layer, layer, s.E, pc[0], pc[1], pc[2], (u32x4*)pool[0],
+                       (u32x4*)(s.n_mats > 1 ? pool[1] : nullptr), (u32x4*)(s.n_mats > 2 ? pool[2] : nullptr));
+    return launch_status();
+}
+
 static int loader_chunks(const mmoe_loader_shape& s, int (&c)[3])
 {
     const int el = s.dtype == MMOE_BF16 ? 8 : 4;

@@ -29,7 +29,7 @@ EXPORTS = [
     "mmoe_workspace_bytes", "mmoe_strerror", "mmoe_pack_weights", "mmoe_route", "mmoe_remap_permute",
     "mmoe_expert_ffn", "mmoe_combine", "mmoe_layer_forward", "mmoe_layer_forward_events",
     "mmoe_layer_forward_static", "mmoe_layer_forward_paged", "mmoe_loader_workspace_bytes", "mmoe_expert_distance", "mmoe_build_expert_map",
-    "mmoe_validate_inputs", "mmoe_probe_ceilings", "mmoe_expert_plan",
+    "mmoe_assemble_pool", "mmoe_validate_inputs", "mmoe_probe_ceilings", "mmoe_expert_plan",
 ]
 
 
@@ -98,6 +98,8 @@ def lib():
         L.mmoe_loader_workspace_bytes.argtypes = [lp]
         L.mmoe_expert_distance.argtypes = [lp, ctypes.POINTER(vp), vp, vp, sz, vp]
         L.mmoe_build_expert_map.argtypes = [lp] + [vp] * 7
+        L.mmoe_assemble_pool.argtypes = [lp, ctypes.POINTER(vp), vp, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.POINTER(vp), vp]
         L.mmoe_expert_plan.argtypes = [sp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.mmoe_probe_ceilings.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_float), vp]
         for n in EXPORTS[2:]:
@@ -308,6 +310,23 @@ def build_expert_map(shape: LoaderShape, distance):
                                        _ptr(rank), _ptr(owner), _ptr(M), _ptr(S), _ptr(src), _stream()),
            "mmoe_build_expert_map")
     return rank, owner, M, S, src
+
+
+def assemble_pool(shape: LoaderShape, mats, slot_src, layer: int, n_slots: int):
+    """The plain pool of one layer, copied from the variants as ``slot_src`` says: list of n_mats device
+    tensors [n_slots, mat_elems[m]]."""
+    dt = _TORCH_DT[shape.dtype]
+    n = shape.V * shape.n_mats
+    ptrs = (ctypes.c_void_p * n)()
+    for v in range(shape.V):
+        for m in range(shape.n_mats):
+            ptrs[v * shape.n_mats + m] = _ptr(mats[v][m], dt, shape.L * shape.E * shape.mat_elems[m], f"mats[{v}][{m}]")
+    pool = [torch.empty((n_slots, shape.mat_elems[m]), dtype=dt, device=mats[0][0].device) for m in range(shape.n_mats)]
+    pp = (ctypes.c_void_p * shape.n_mats)(*[p.data_ptr() for p in pool])
+    _check(lib().mmoe_assemble_pool(ctypes.byref(shape), ptrs,
+                                    _ptr(slot_src, torch.int32, shape.L * shape.V * shape.E * 2, "slot_src"),
+                                    int(layer), int(n_slots), pp, _stream()), "mmoe_assemble_pool")
+    return pool
 
 
 def layer_forward_paged(shape: Shape, X, vid, Wr, br, M, W1p, W3p, W2p, resident, host_pool, ws, copy_stream,

@@ -117,9 +117,12 @@ def test_emitted_table_drives_the_layer(mm, oracle):
     S_l = int(S[layer])
     src_l = src[layer, :S_l].cpu().numpy()
     d, f = cfg.d_model, cfg.d_ff
-    # pool assembly is a copy of stored weights (no arithmetic): slot s <- expert src_l[s] of the layer
+    # pool assembly is a copy of stored weights (no arithmetic): slot s <- expert src_l[s] of the layer;
+    # the library's copy kernel against the same thing written with numpy indexing
     pool = [np.stack([variants[v][m][layer, e] for v, e in src_l]).reshape(S_l, *shp)
             for m, shp in ((0, (d, f)), (1, (d, f)), (2, (f, d)))]
+    for m, got in enumerate(mm.assemble_pool(sh, dev, src, layer, S_l)):
+        assert np.array_equal(gc.bits(got).reshape(pool[m].shape), pool[m]), f"assembled pool, matrix {m}"
     lcfg = synth.Config("tb_layer_fwd", 200, d, f, cfg.V, cfg.E, 2, "bf16", "swiglu", seed=10)
     inp = synth.make_inputs(lcfg, weights=False)
     inp.update(M=ref["M"][layer].copy(), S=S_l, W1=pool[0], W3=pool[1], W2=pool[2])

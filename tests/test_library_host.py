@@ -132,6 +132,11 @@ def test_expert_map_builder_argument_checks(mm):
         assert L.mmoe_loader_workspace_bytes(ctypes.byref(shape)) == 0
         assert L.mmoe_build_expert_map(ctypes.byref(shape), p, p, p, p, p, p, None) == code
     assert L.mmoe_build_expert_map(ctypes.byref(ok), p, p, None, p, p, p, None) == -1
+    pool = (ctypes.c_void_p * 2)(4096, 4096)
+    assert L.mmoe_assemble_pool(ctypes.byref(ok), ptrs, p, 3, 4, pool, None) == -2      # layer out of range
+    assert L.mmoe_assemble_pool(ctypes.byref(ok), ptrs, p, 0, 9, pool, None) == -2      # more slots than V*E
+    assert L.mmoe_assemble_pool(ctypes.byref(ok), ptrs, None, 0, 4, pool, None) == -1
+    assert L.mmoe_assemble_pool(ctypes.byref(ok), ptrs, p, 0, 4, (ctypes.c_void_p * 2)(4096, 4100), None) == -7
 
 
 def test_binding_refuses_host_tensors(mm):
