@@ -31,7 +31,10 @@
 
 namespace mmoe {
 
-enum { kModeReluH = 0, kModeSwigluH = 1, kModePlainF32 = 2, kModeGeluH = 3 };
+// What a product writes: H = act(.) in the storage type (up product), plain fp32 rows of Yg (down
+// product), or, for layers with top_k = 1, the layer's output rows themselves: 0 + w[token] * y in the
+// storage type at row token (GateSink).
+enum { kModeReluH = 0, kModeSwigluH = 1, kModePlainF32 = 2, kModeGeluH = 3, kModeGatedY = 4 };
 
 constexpr int kSkThreads = 256;
 constexpr int kSkWaves = 4;
@@ -117,7 +120,9 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
                                                             const int32_t* __restrict__ offsets,
                                                             const int32_t* __restrict__ slot_of_pair, int P,
                                                             const T* __restrict__ W0, const T* __restrict__ W1,
-                                                            void* __restrict__ out, int K, int N, SlotFilter filt)
+                                                            void* __restrict__ out, int K, int N, SlotFilter filt,
+                                                            const int32_t* __restrict__ sink_perm,
+                                                            const float* __restrict__ sink_w)
 {
     constexpr int EPB = 16 / (int)sizeof(T);  // elements per 16-byte piece
     constexpr int KSS = 16 * EPB;             // elements per 256-byte step
@@ -213,14 +218,21 @@ __global__ __launch_bounds__(kSkThreads) void skinny_kernel(const T* __restrict_
         // accumulator element i of lane l is output feature n0 + 4*(l/16) + i of token column l%16
         auto finish = [&](int row, int l, const float (&v)[NW][4]) {
             float o[4];
+            int orow = rs.out_row(row);
+            float gw = 0.0f;
+            if (MODE == kModeGatedY) {
+                if (sink_perm) orow = sink_perm[orow];
+                gw = sink_w[orow];
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if (MODE == kModeSwigluH) o[i] = silu_mul(v[0][i], v[NW - 1][i]);
                 else if (MODE == kModeReluH) o[i] = fmaxf(v[0][i], 0.0f);
                 else if (MODE == kModeGeluH) o[i] = gelu(v[0][i]);
+                else if (MODE == kModeGatedY) o[i] = __builtin_fmaf(gw, v[0][i], 0.0f);
                 else o[i] = v[0][i];
             }
-            const size_t at = (size_t)rs.out_row(row) * N + n0 + 4 * (l >> 4);
+            const size_t at = (size_t)orow * N + n0 + 4 * (l >> 4);
             if (MODE == kModePlainF32 || sizeof(T) == 4) {
                 *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = f32x4{o[0], o[1], o[2], o[3]};
             } else {
@@ -285,7 +297,9 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
                                                                  const uint16_t* __restrict__ W0,
                                                                  const uint16_t* __restrict__ W1,
                                                                  void* __restrict__ out, int K, int N,
-                                                                 SlotFilter filt)
+                                                                 SlotFilter filt,
+                                                                 const int32_t* __restrict__ sink_perm,
+                                                                 const float* __restrict__ sink_w)
 {
     __shared__ float red[kSkWaves][NW][kWave][16];  // 16 KB per matrix
     __shared__ int mine[kSelfMaxP];
@@ -376,6 +390,12 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
             const int row = pass0 + (l & 31);
             if (row < cnt) {
                 float o[4];
+                int orow = rs.out_row(row);
+                float gw = 0.0f;
+                if (MODE == kModeGatedY) {
+                    if (sink_perm) orow = sink_perm[orow];
+                    gw = sink_w[orow];
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int e = 4 * q + i;
@@ -386,9 +406,10 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
                     if (MODE == kModeSwigluH) o[i] = silu_mul(v[0], v[NW - 1]);
                     else if (MODE == kModeReluH) o[i] = fmaxf(v[0], 0.0f);
                     else if (MODE == kModeGeluH) o[i] = gelu(v[0]);
+                    else if (MODE == kModeGatedY) o[i] = __builtin_fmaf(gw, v[0], 0.0f);
                     else o[i] = v[0];
                 }
-                const size_t at = (size_t)rs.out_row(row) * N + nb * 32 + 8 * q + 4 * (l >> 5);
+                const size_t at = (size_t)orow * N + nb * 32 + 8 * q + 4 * (l >> 5);
                 if (MODE == kModePlainF32) {
                     *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(out) + at) = f32x4{o[0], o[1], o[2], o[3]};
                 } else {
@@ -405,8 +426,10 @@ __global__ __launch_bounds__(kSkThreads) void skinny_frag_kernel(const uint16_t*
 
 static int run_skinny_bf16(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                            const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H,
-                           float* Yg, hipStream_t st, hipEvent_t mid, SlotFilter filt)
+                           float* Yg, hipStream_t st, hipEvent_t mid, SlotFilter filt, GateSink sink)
 {
+    const int32_t* nosink = nullptr;
+    const float* now = nullptr;
     const int32_t* noperm = nullptr;
     const int d = s.d_model, f = s.d_ff, P = s.T * s.top_k;
     dim3 block(kSkThreads);
@@ -414,16 +437,21 @@ static int run_skinny_bf16(const mmoe_shape& s, const void* rows, const int32_t*
     const uint16_t* nul = nullptr;
     if (s.act == MMOE_SWIGLU)
         hipLaunchKernelGGL((skinny_frag_kernel<2, 1, kModeSwigluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
-                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, filt);
+                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, (const uint16_t*)W3p, H, d, f, filt,
+                           nosink, now);
     else if (s.act == MMOE_GELU)
         hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeGeluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
-                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f, filt);
+                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f, filt, nosink, now);
     else
         hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeReluH>), g1, block, 0, st, (const uint16_t*)rows, perm,
-                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f, filt);
+                           s.top_k, offsets, slot_of_pair, P, (const uint16_t*)W1p, nul, H, d, f, filt, nosink, now);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModePlainF32>), g2, block, 0, st, (const uint16_t*)H, noperm, 1,
-                       offsets, slot_of_pair, P, (const uint16_t*)W2p, nul, (void*)Yg, f, d, filt);
+    if (sink.w)
+        hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModeGatedY>), g2, block, 0, st, (const uint16_t*)H, noperm, 1,
+                           offsets, slot_of_pair, P, (const uint16_t*)W2p, nul, sink.Y, f, d, filt, sink.perm, sink.w);
+    else
+        hipLaunchKernelGGL((skinny_frag_kernel<1, 2, kModePlainF32>), g2, block, 0, st, (const uint16_t*)H, noperm, 1,
+                           offsets, slot_of_pair, P, (const uint16_t*)W2p, nul, (void*)Yg, f, d, filt, nosink, now);
     return launch_status();
 }
 
@@ -431,8 +459,10 @@ template <typename T, bool SPLITK>
 static void launch_skinny_products(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                                    const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p,
                                    void* H, float* Yg, hipStream_t st, hipEvent_t mid, SlotFilter filt, bool up,
-                                   bool down)
+                                   bool down, GateSink sink)
 {
+    const int32_t* nosink = nullptr;
+    const float* now = nullptr;
     const int32_t* noperm = nullptr;
     const int d = s.d_model, f = s.d_ff, P = s.T * s.top_k;
     constexpr int kFeat = SPLITK ? 16 : 16 * kSkWaves;  // output features per workgroup
@@ -442,17 +472,21 @@ static void launch_skinny_products(const mmoe_shape& s, const void* rows, const 
     if (up) {
         if (s.act == MMOE_SWIGLU)
             hipLaunchKernelGGL((skinny_kernel<T, 2, 1, kModeSwigluH, SPLITK>), g1, block, 0, st, (const T*)rows, perm,
-                               s.top_k, offsets, slot_of_pair, P, (const T*)W1p, (const T*)W3p, H, d, f, filt);
+                               s.top_k, offsets, slot_of_pair, P, (const T*)W1p, (const T*)W3p, H, d, f, filt,
+                               nosink, now);
         else if (s.act == MMOE_GELU)
             hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeGeluH, SPLITK>), g1, block, 0, st, (const T*)rows, perm,
-                               s.top_k, offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt);
+                               s.top_k, offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt, nosink, now);
         else
             hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeReluH, SPLITK>), g1, block, 0, st, (const T*)rows, perm,
-                               s.top_k, offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt);
+                               s.top_k, offsets, slot_of_pair, P, (const T*)W1p, nul, H, d, f, filt, nosink, now);
     }
-    if (down)
+    if (down && sink.w)
+        hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModeGatedY, SPLITK>), g2, block, 0, st, (const T*)H, noperm, 1,
+                           offsets, slot_of_pair, P, (const T*)W2p, nul, sink.Y, f, d, filt, sink.perm, sink.w);
+    else if (down)
         hipLaunchKernelGGL((skinny_kernel<T, 1, 2, kModePlainF32, SPLITK>), g2, block, 0, st, (const T*)H, noperm, 1,
-                           offsets, slot_of_pair, P, (const T*)W2p, nul, (void*)Yg, f, d, filt);
+                           offsets, slot_of_pair, P, (const T*)W2p, nul, (void*)Yg, f, d, filt, nosink, now);
     (void)mid;
 }
 
@@ -463,21 +497,21 @@ static bool whole_k(int K) { return K <= 1024; }
 template <typename T>
 static int run_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                       const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg,
-                      hipStream_t st, hipEvent_t mid, SlotFilter filt)
+                      hipStream_t st, hipEvent_t mid, SlotFilter filt, GateSink sink)
 {
     if (whole_k(s.d_model))
         launch_skinny_products<T, false>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, true,
-                                         false);
+                                         false, sink);
     else
         launch_skinny_products<T, true>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, true,
-                                        false);
+                                        false, sink);
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
     if (whole_k(s.d_ff))
         launch_skinny_products<T, false>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, false,
-                                         true);
+                                         true, sink);
     else
         launch_skinny_products<T, true>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, false,
-                                        true);
+                                        true, sink);
     return launch_status();
 }
 
@@ -488,12 +522,14 @@ bool self_grouping(const mmoe_shape& s)
 
 int launch_ffn_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                       const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H,
-                      float* Yg, hipStream_t st, hipEvent_t mid, SlotFilter filt)
+                      float* Yg, hipStream_t st, hipEvent_t mid, SlotFilter filt, GateSink sink)
 {
     if (slot_of_pair && (int64_t)s.T * s.top_k > kSelfMaxP) return MMOE_ERR_LIMIT;
+    // gated output rows: one pick per token; the grouped form needs the permutation, the self-grouping form must not have one
+    if (sink.w && (s.top_k != 1 || !sink.Y || (slot_of_pair != nullptr) != (sink.perm == nullptr))) return MMOE_ERR_DIM;
     if (s.dtype == MMOE_BF16)
-        return run_skinny_bf16(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt);
-    return run_skinny<float>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt);
+        return run_skinny_bf16(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, sink);
+    return run_skinny<float>(s, rows, perm, offsets, slot_of_pair, W1p, W3p, W2p, H, Yg, st, mid, filt, sink);
 }
 
 }  // namespace mmoe

@@ -33,7 +33,9 @@
 
 namespace mmoe {
 
-enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2, kTModeGeluH = 3 };
+// What a product writes: H = act(.) in bf16 (up product), plain fp32 rows of Yg (down product), or,
+// for layers with top_k = 1, the layer's output rows: 0 + w[token] * y in bf16 at row token (GateSink).
+enum { kTModeReluH = 0, kTModeSwigluH = 1, kTModePlainF32 = 2, kTModeGeluH = 3, kTModeGatedY = 4 };
 
 constexpr int kBN = 256;  // weight rows per tile: four wavefronts of two 32-row blocks (128 with one block each)
 constexpr int kBK = 64;
@@ -62,7 +64,9 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
                                                             const int32_t* __restrict__ tab, int hdr, int list_hi,
                                                             int list_lo, const uint16_t* __restrict__ W0,
                                                             const uint16_t* __restrict__ W1,
-                                                            void* __restrict__ out, int K, int N, int NT)
+                                                            void* __restrict__ out, int K, int N, int NT,
+                                                            const int32_t* __restrict__ sink_perm,
+                                                            const float* __restrict__ sink_w)
 {
     constexpr int kTileBytes = BM * kBK * 2;  // one step of the token operand (32 KB for 256 rows)
     __shared__ __attribute__((aligned(1024))) char lds_a[kStagesA * kTileBytes];
@@ -157,6 +161,27 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
         frag_off[kk] = lr * 128 + ((((lane >> 5) * 4 + kk) ^ ((lr >> 1) & 7)) << 4);
+
+    // Gated output rows (GateSink): the coefficient of this lane's token column of every sub-tile, and
+    // the output row (token) of every row this lane stores in the epilogue.  Two dependent loads each;
+    // short-lived 128-row tiles start them here, behind the main loop's own loads, tall tiles (no
+    // registers to spare in the main loop, and an epilogue that is a hundredth of the tile) when
+    // the main loop is over.
+    constexpr int kSinkLpr = 4;   // lanes per stored row of 32 bf16 features (the epilogue's kLpr)
+    constexpr int kSinkRpi = 16;  // rows per store instruction (its kRpi)
+    constexpr bool kEarlySink = BM == kBMSmall;
+    float gate_w[kNJ];
+    int sink_row[kNJ][32 / kSinkRpi];
+    auto fetch_sink = [&]() {
+#pragma unroll
+        for (int j = 0; j < kNJ; ++j) {
+            gate_w[j] = sink_w[sink_perm[r0 + min(j * 32 + lr, cnt - 1)]];
+#pragma unroll
+            for (int it = 0; it < 32 / kSinkRpi; ++it)
+                sink_row[j][it] = sink_perm[r0 + min(j * 32 + it * kSinkRpi + lane / kSinkLpr, cnt - 1)];
+        }
+    };
+    if (MODE == kTModeGatedY && kEarlySink) fetch_sink();
 
     f32x16 acc[kNJ][NB];  // [token sub-tile][weight block]
 #pragma unroll
@@ -332,6 +357,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
     constexpr int kPitch = kRowB + 16;                // padded: conflict-free 16-byte column writes
     constexpr int kLpr = kRowB / 16;                  // lanes that read one row back
     constexpr int kRpi = 64 / kLpr;                   // rows per read-back instruction
+    static_assert(MODE != kTModeGatedY || (kLpr == kSinkLpr && kRpi == kSinkRpi), "the sink rows follow the stores");
     constexpr int kChunks = MODE == kTModeSwigluH ? 1 : NB;       // 32-feature chunks this wavefront stores
     const int wfeat = MODE == kTModeSwigluH ? wn * 32 : wn * (32 * NB);
     // the patches reuse the token ring: every wavefront has left the main loop
@@ -339,6 +365,8 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
     char* ebuf = lds_a + wave * (32 * (32 * 4 + 16));
     char* const obase = reinterpret_cast<char*>(out) + ((size_t)r0 * N + n0 + wfeat) * kEsz +
                         (size_t)(lane / kLpr) * N * kEsz + (lane % kLpr) * 16;
+    if (MODE == kTModeGatedY && !kEarlySink) fetch_sink();
+    char* const ybase = reinterpret_cast<char*>(out) + (size_t)(n0 + wfeat) * kEsz + (lane % kLpr) * 16;
     // o[4q + e]: the 16 finished values of this lane for token sub-tile j, feature chunk c
     auto emit = [&](int j, int c, const float (&o)[16]) {
 #pragma unroll
@@ -357,8 +385,11 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
         for (int it = 0; it < 32 / kRpi; ++it) {
             const int row = it * kRpi + lane / kLpr;
             const u32x4 v = *reinterpret_cast<const u32x4*>(ebuf + row * kPitch + (lane % kLpr) * 16);
-            if (j * 32 + row < cnt)
-                *reinterpret_cast<u32x4*>(obase + ((size_t)(j * 32 + it * kRpi) * N + c * 32) * kEsz) = v;
+            if (j * 32 + row < cnt) {
+                char* dst = MODE == kTModeGatedY ? ybase + ((size_t)sink_row[j][it % (32 / kSinkRpi)] * N + c * 32) * kEsz
+                                                 : obase + ((size_t)(j * 32 + it * kRpi) * N + c * 32) * kEsz;
+                *reinterpret_cast<u32x4*>(dst) = v;
+            }
         }
     };
 #pragma unroll
@@ -372,6 +403,7 @@ __global__ __launch_bounds__(256, BM == kBMBig ? 1 : 2) void tiled_kernel(const 
                 if (MODE == kTModeSwigluH) o[e] = silu_mul_t(acc[j][0][e], acc[j][NB - 1][e]);
                 else if (MODE == kTModeReluH) o[e] = fmaxf(acc[j][c][e], 0.0f);
                 else if (MODE == kTModeGeluH) o[e] = 0.5f * acc[j][c][e] * (1.0f + erff(acc[j][c][e] * 0.70710678118654752440f));
+                else if (MODE == kTModeGatedY) o[e] = __builtin_fmaf(gate_w[j], acc[j][c][e], 0.0f);
                 else o[e] = acc[j][c][e];
             }
             emit(j, c, o);
@@ -443,22 +475,24 @@ size_t tiled_table_bytes(const mmoe_shape& s)
 
 template <int MODE, int BM, int NB>
 static void launch_product(const TiledPlan& p, int prod, const void* A, const int32_t* perm, int kdiv, const int32_t* tab,
-                           const void* W0, const void* W1, void* out, int K, int N, hipStream_t st)
+                           const void* W0, const void* W1, void* out, int K, int N, hipStream_t st,
+                           GateSink sink = GateSink())
 {
     hipLaunchKernelGGL((tiled_kernel<MODE, BM, NB>), dim3(p.L.cap[prod] * kXcds), dim3(256), 0, st, (const uint16_t*)A,
                        perm, kdiv, tab, p.L.hdr + prod, p.L.list[prod][0], p.L.list[prod][1], (const uint16_t*)W0,
-                       (const uint16_t*)W1, out, K, N, prod == 0 ? p.nt_up : p.nt_down);
+                       (const uint16_t*)W1, out, K, N, prod == 0 ? p.nt_up : p.nt_down, sink.perm, sink.w);
 }
 
 // one weight block per wavefront exists for 128-row tiles only (planned_nb)
 template <int MODE>
 static void launch_plain_product(const TiledPlan& p, int prod, const void* A, const int32_t* perm, int kdiv,
-                                 const int32_t* tab, const void* W0, void* out, int K, int N, hipStream_t st)
+                                 const int32_t* tab, const void* W0, void* out, int K, int N, hipStream_t st,
+                                 GateSink sink = GateSink())
 {
     const int nb = prod == 0 ? p.nb_up : p.nb_down;
-    if (p.bm == kBMBig) launch_product<MODE, kBMBig, 2>(p, prod, A, perm, kdiv, tab, W0, nullptr, out, K, N, st);
-    else if (nb == 2) launch_product<MODE, kBMSmall, 2>(p, prod, A, perm, kdiv, tab, W0, nullptr, out, K, N, st);
-    else launch_product<MODE, kBMSmall, 1>(p, prod, A, perm, kdiv, tab, W0, nullptr, out, K, N, st);
+    if (p.bm == kBMBig) launch_product<MODE, kBMBig, 2>(p, prod, A, perm, kdiv, tab, W0, nullptr, out, K, N, st, sink);
+    else if (nb == 2) launch_product<MODE, kBMSmall, 2>(p, prod, A, perm, kdiv, tab, W0, nullptr, out, K, N, st, sink);
+    else launch_product<MODE, kBMSmall, 1>(p, prod, A, perm, kdiv, tab, W0, nullptr, out, K, N, st, sink);
 }
 
 TileJob tile_job(const mmoe_shape& s, int32_t* tab)
@@ -475,7 +509,7 @@ TileJob tile_job(const mmoe_shape& s, int32_t* tab)
 
 int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
-                     hipStream_t st, hipEvent_t mid, bool tab_ready, SlotFilter filt)
+                     hipStream_t st, hipEvent_t mid, bool tab_ready, SlotFilter filt, GateSink sink)
 {
     if (s.dtype != MMOE_BF16) return MMOE_ERR_DTYPE;
     const int P = s.T * s.top_k, d = s.d_model, f = s.d_ff;
@@ -495,7 +529,12 @@ int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm,
         launch_plain_product<kTModeReluH>(p, 0, rows, perm, s.top_k, tab, W1p, H, d, f, st);
     }
     if (mid && hipEventRecord(mid, st) != hipSuccess) return MMOE_ERR_LAUNCH;
-    launch_plain_product<kTModePlainF32>(p, 1, H, nullptr, 1, tab, W2p, Yg, f, d, st);
+    if (sink.w) {
+        if (s.top_k != 1 || !sink.perm || !sink.Y) return MMOE_ERR_DIM;
+        launch_plain_product<kTModeGatedY>(p, 1, H, nullptr, 1, tab, W2p, sink.Y, f, d, st, sink);
+    } else {
+        launch_plain_product<kTModePlainF32>(p, 1, H, nullptr, 1, tab, W2p, Yg, f, d, st);
+    }
     return launch_status();
 }
 

@@ -204,6 +204,14 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
     int32_t* inv_perm = (int32_t*)(w + L.inv_perm);
     float* Yg = (float*)(w + L.Yg);
     hipEvent_t mid = events ? (hipEvent_t)events[MMOE_EV_FFN_UP] : nullptr;  // may be null
+    // One pick per token: the combination is one product per element, and the down product's epilogue
+    // applies it and writes Y itself (same arithmetic as the combination kernel: bit-identical).
+    const bool fold = shape->top_k == 1;
+    GateSink sink;
+    if (fold) {
+        sink.Y = Y;
+        sink.w = topk_w;
+    }
 
     if ((rc = mark(MMOE_EV_START))) return rc;
     if (self_grouping(*shape)) {
@@ -214,9 +222,10 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
         if ((rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st, M, slot))) return rc;
         if ((rc = mark(MMOE_EV_ROUTE))) return rc;
         if ((rc = mark(MMOE_EV_PERMUTE))) return rc;
-        if ((rc = launch_ffn_skinny(*shape, X, nullptr, nullptr, slot, W1p, W3p, W2p, w + L.H, Yg, st, mid))) return rc;
+        rc = launch_ffn_skinny(*shape, X, nullptr, nullptr, slot, W1p, W3p, W2p, w + L.H, Yg, st, mid, SlotFilter(), sink);
+        if (rc) return rc;
         if ((rc = mark(MMOE_EV_FFN_DOWN))) return rc;
-        if ((rc = launch_combine(*shape, Yg, nullptr, topk_w, Y, st))) return rc;
+        if (!fold && (rc = launch_combine(*shape, Yg, nullptr, topk_w, Y, st))) return rc;
         return mark(MMOE_EV_COMBINE);
     }
     if ((rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st))) return rc;
@@ -230,13 +239,15 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
                         st, tiled ? tile_tab : nullptr);
     if (rc) return rc;
     if ((rc = mark(MMOE_EV_PERMUTE))) return rc;
+    sink.perm = perm;
     if (!tiled)
-        rc = launch_ffn_skinny(*shape, X, perm, offsets, nullptr, W1p, W3p, W2p, w + L.H, Yg, st, mid);
+        rc = launch_ffn_skinny(*shape, X, perm, offsets, nullptr, W1p, W3p, W2p, w + L.H, Yg, st, mid, SlotFilter(), sink);
     else
-        rc = launch_ffn_tiled(*shape, X, perm, offsets, W1p, W3p, W2p, w + L.H, Yg, tile_tab, st, mid, true);
+        rc = launch_ffn_tiled(*shape, X, perm, offsets, W1p, W3p, W2p, w + L.H, Yg, tile_tab, st, mid, true,
+                              SlotFilter(), sink);
     if (rc) return rc;
     if ((rc = mark(MMOE_EV_FFN_DOWN))) return rc;
-    if ((rc = launch_combine(*shape, Yg, inv_perm, topk_w, Y, st))) return rc;
+    if (!fold && (rc = launch_combine(*shape, Yg, inv_perm, topk_w, Y, st))) return rc;
     return mark(MMOE_EV_COMBINE);
 }
 
@@ -316,19 +327,27 @@ int mmoe_layer_forward_paged(const mmoe_shape* shape, const void* X, const int32
     // hits first (they overlap the copies), then the slots that have just arrived
     const bool tiled = !use_skinny(*shape);
     int32_t* tile_tab = (int32_t*)(w + L.tile_tab);
+    const bool fold = shape->top_k == 1;  // the down product writes Y itself (see mmoe_layer_forward_events)
+    GateSink sink;
+    if (fold) {
+        sink.Y = Y;
+        sink.w = topk_w;
+        sink.perm = perm;
+    }
     for (int pass = 0; pass < (n_missed ? 2 : 1); ++pass) {
         SlotFilter filt;
         filt.flag = res_dev;
         filt.want = pass == 0 ? 1 : 0;
         if (pass == 1 && hipStreamWaitEvent(st, ev_copied, 0) != hipSuccess) return done(MMOE_ERR_LAUNCH);
         if (!tiled)
-            rc = launch_ffn_skinny(*shape, X, perm, offsets, nullptr, W1p, W3p, W2p, w + L.H, Yg, st, nullptr, filt);
+            rc = launch_ffn_skinny(*shape, X, perm, offsets, nullptr, W1p, W3p, W2p, w + L.H, Yg, st, nullptr, filt,
+                                   sink);
         else
             rc = launch_ffn_tiled(*shape, X, perm, offsets, W1p, W3p, W2p, w + L.H, Yg, tile_tab, st, nullptr, false,
-                                  filt);
+                                  filt, sink);
         if (rc) return done(rc);
     }
-    if ((rc = launch_combine(*shape, Yg, inv_perm, topk_w, Y, st))) return done(rc);
+    if (!fold && (rc = launch_combine(*shape, Yg, inv_perm, topk_w, Y, st))) return done(rc);
     return done(n_missed);
 }
 

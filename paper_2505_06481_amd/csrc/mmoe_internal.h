@@ -45,6 +45,16 @@ struct SlotFilter {
     __host__ __device__ bool skips(int s) const { return flag && flag[s] != want; }
 };
 
+// Where the rows of the down product go.  Default (`w` null): row r of Yg, fp32.  With `w` (layers
+// with top_k = 1, whose combination is a single product per element): row token(r) of Y in the storage
+// type, holding 0 + w[token] * y -- the value the combination kernel computes for one pick -- so that
+// kernel and the round trip of Yg through memory are not needed.
+struct GateSink {
+    void* Y = nullptr;              // DEVICE [T, d_model] dtype
+    const float* w = nullptr;       // DEVICE topk_w [T]
+    const int32_t* perm = nullptr;  // grouped row -> pair id (= token when top_k = 1); null: rows are indexed by pair id
+};
+
 // Sub-buffers of the caller's workspace used by mmoe_layer_forward (byte offsets).
 struct WsLayout {
     size_t topk_idx, topk_w, slot, counts, offsets, perm, inv_perm, blk_counts, blk_base, tile_tab, resident, H, Yg,
@@ -73,12 +83,14 @@ int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const
 // Expert stage.  Row r of the grouped input is rows[r] when `perm` is null (rows = Xg), and
 // rows[perm[r] / top_k] otherwise (rows = X: the gather is folded into the up product's loads).
 // `mid`, when not null, is recorded between the up product (+ activation) and the down product.
+// `sink` with `w` set: the down product writes the layer's output rows itself (see GateSink), Yg is unused.
 // `slot_of_pair` given (self-grouping, only when self_grouping(s)): no grouping has run; every
 // workgroup collects the pairs of its slot from slot_of_pair[P] itself, rows = X, and H and Yg are
 // indexed by pair id; `perm` and `offsets` are then unused.
 int launch_ffn_skinny(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                       const int32_t* slot_of_pair, const void* W1p, const void* W3p, const void* W2p, void* H,
-                      float* Yg, hipStream_t st, hipEvent_t mid = nullptr, SlotFilter filt = SlotFilter());
+                      float* Yg, hipStream_t st, hipEvent_t mid = nullptr, SlotFilter filt = SlotFilter(),
+                      GateSink sink = GateSink());
 // true when the fused layer skips the grouping kernels (streaming expert kernels, few pairs)
 bool self_grouping(const mmoe_shape& s);
 // `tab`: tiled_table_bytes() of scratch for the row-tile table.
@@ -86,7 +98,7 @@ bool self_grouping(const mmoe_shape& s);
 int launch_ffn_tiled(const mmoe_shape& s, const void* rows, const int32_t* perm, const int32_t* offsets,
                      const void* W1p, const void* W3p, const void* W2p, void* H, float* Yg, int32_t* tab,
                      hipStream_t st, hipEvent_t mid = nullptr, bool tab_ready = false,
-                     SlotFilter filt = SlotFilter());
+                     SlotFilter filt = SlotFilter(), GateSink sink = GateSink());
 size_t tiled_table_bytes(const mmoe_shape& s);
 int planned_tile_rows(const mmoe_shape& s);  // tile height launch_ffn_tiled would use for this shape
 // `inv_perm` null: Yg is indexed by pair id.

@@ -85,6 +85,12 @@ SMALL = [
     # batches large enough for the wavefront-per-token router, odd expert counts, fp32 and bf16
     synth.Config("r_f32_odd_e", 2100, 512, 256, 2, 5, 2, "f32", "swiglu", seed=17, bias_alpha=0.7),
     synth.Config("r_bf16_odd_e", 2060, 1536, 256, 3, 7, 2, "bf16", "relu", seed=18, bias_alpha=0.3),
+    # one pick per token (the down product writes the layer's output rows itself) where the grouping
+    # kernels have run: streaming kernels in fp32 and, with many slots, in bf16; matrix-core kernels at
+    # both tile heights are t_bf16_relu
+    synth.Config("k1_f32_grouped", 1500, 256, 512, 2, 6, 1, "f32", "gelu", seed=27),
+    synth.Config("k1_bf16_grouped_stream", 1300, 512, 256, 8, 16, 1, "bf16", "relu", seed=28, share_prob=0.1),
+    synth.Config("k1_bf16_long_k", 1100, 2048, 256, 2, 4, 1, "bf16", "relu", seed=29),     # tall-tile shape rule
 ]
 
 

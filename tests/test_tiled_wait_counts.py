@@ -170,7 +170,7 @@ def test_every_written_out_wait_of_the_tiled_kernel_is_covered():
     fns = functions(text, "_ZN4mmoe12tiled_kernel")
     # 4 products (three activations, down) x 2 tile heights, and the three products without a gate
     # once more with one weight block per wavefront (128-row tiles only)
-    assert len(fns) == 11, [f.name for f in fns]
+    assert len(fns) == 14, [f.name for f in fns]
     for fn in fns:
         bm, nb = (int(x) for x in re.search(r"ILi\d+ELi(\d+)ELi(\d+)EE", fn.name).groups())
         knp = bm * 8 // 256                               # copies per wavefront and step
