@@ -6,7 +6,8 @@
 // Deterministic by construction: the rank of pair p inside its slot is the number of
 // lower pair ids with the same slot, computed from wavefront ballots and integer
 // prefix sums.  There are no cursors bumped by atomics and no waiting between
-// workgroups: three short kernels (histogram, scan, scatter) and one gather.
+// workgroups: three short kernels (histogram, scan, scatter; two when the scatter workgroups can
+// afford to sum the histograms themselves) and one gather.
 //
 // Work split: workgroup b owns pairs [b*2048, (b+1)*2048); inside it wavefront w owns a
 // contiguous quarter, walked 64 pairs at a time in ascending order.
@@ -19,6 +20,8 @@ constexpr int kPermThreads = 256;
 static_assert(kPermThreads == 256, "build_tile_lists is written for one workgroup of 256 threads");
 constexpr int kPermWaves = kPermThreads / kWave;
 constexpr int kPairsPerWave = kPermChunk / kPermWaves;  // 512
+constexpr int kOwnScanMax = 1 << 14;  // most per-workgroup counts (workgroups x slots) a scatter workgroup sums by itself
+static_assert(kMaxS % kPermThreads == 0, "slots per thread");
 
 // slot[p] = M[vid[p / k]][topk_idx[p]]; per-workgroup histogram of the slots.
 __global__ __launch_bounds__(kPermThreads) void slot_hist_kernel(
@@ -121,16 +124,71 @@ __device__ __forceinline__ void place_pairs(volatile int* cur, int s, bool valid
 }
 
 // perm / inv_perm: stable ranks from ballots.
+// SCAN = false: the first output row of this workgroup's pairs of every slot comes from `blk_base`
+// (written by slot_scan_kernel).  SCAN = true (few workgroups, few slots: the table of per-workgroup
+// counts is small): every workgroup sums that table itself, so the scan kernel and its launch are not
+// needed; the grid has one more workgroup, which places no pairs and writes counts, offsets and the
+// tile lists instead.
+template <bool SCAN>
 __global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_t* __restrict__ slot,
                                                                     const int32_t* __restrict__ blk_base,
+                                                                    const int32_t* __restrict__ blk_counts, int nblk,
+                                                                    int32_t* __restrict__ counts,
+                                                                    int32_t* __restrict__ offsets,
                                                                     int32_t* __restrict__ perm,
-                                                                    int32_t* __restrict__ inv_perm, int P, int S)
+                                                                    int32_t* __restrict__ inv_perm, int P, int S,
+                                                                    TileJob tiles)
 {
     __shared__ int wtot[kPermWaves][kMaxS];  // pairs of each slot owned by each wavefront
     __shared__ int cursor[kPermWaves][kMaxS];
+    __shared__ int tot[SCAN ? kMaxS : 1];      // pairs of each slot in the whole batch, then its first row
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int sbits = 32 - __clz(max(S - 1, 1));  // bits of a slot id
+    int before[kMaxS / kPermThreads];             // this workgroup's first row of slot threadIdx.x + 256 i
+    if (SCAN) {
+        const int b = blockIdx.x;  // nblk: the workgroup that writes the tables
+#pragma unroll
+        for (int i = 0; i < kMaxS / kPermThreads; ++i) {
+            const int sl = threadIdx.x + i * kPermThreads;
+            int run = 0, mine = 0;
+            if (sl < S)
+                for (int bb = 0; bb < nblk; ++bb) {
+                    if (bb == b) mine = run;
+                    run += blk_counts[(size_t)bb * S + sl];
+                }
+            before[i] = mine;
+            if (sl < S) tot[sl] = run;
+        }
+        __syncthreads();
+        if (b == nblk)
+            for (int sl = threadIdx.x; sl < S; sl += kPermThreads) counts[sl] = tot[sl];
+        __syncthreads();
+        if (threadIdx.x < kWave) {  // exclusive scan of the S totals, 64 at a time; tot[s] becomes offsets[s]
+            int carry = 0;
+            for (int s0 = 0; s0 < S; s0 += kWave) {
+                const int sl = s0 + threadIdx.x;
+                const int c = sl < S ? tot[sl] : 0;
+                int incl = c;
+#pragma unroll
+                for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+                    const int o = __shfl_up(incl, dlt, kWave);
+                    if ((int)threadIdx.x >= dlt) incl += o;
+                }
+                if (sl < S) {
+                    tot[sl] = carry + incl - c;
+                    if (b == nblk) offsets[sl] = carry + incl - c;
+                }
+                carry += __shfl(incl, kWave - 1, kWave);
+            }
+            if (b == nblk && threadIdx.x == 0) offsets[S] = carry;
+        }
+        __syncthreads();
+        if (b == nblk) {  // uniform over the workgroup
+            if (tiles.tab) build_tile_lists(offsets, tiles.tab, S, tiles.nt_up, tiles.nt_down, tiles.bm, tiles.L);
+            return;
+        }
+    }
     for (int i = threadIdx.x; i < kPermWaves * S; i += kPermThreads) wtot[i / S][i % S] = 0;
     __syncthreads();
     const int wbase = blockIdx.x * kPermChunk + wave * kPairsPerWave;
@@ -139,12 +197,16 @@ __global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_
         if (p < P) atomicAdd(&wtot[wave][slot[p]], 1);
     }
     __syncthreads();
-    for (int s = threadIdx.x; s < S; s += kPermThreads) {
-        int run = blk_base[(size_t)blockIdx.x * S + s];
 #pragma unroll
-        for (int w = 0; w < kPermWaves; ++w) {
-            cursor[w][s] = run;
-            run += wtot[w][s];
+    for (int i = 0; i < kMaxS / kPermThreads; ++i) {
+        const int s = threadIdx.x + i * kPermThreads;
+        if (s < S) {
+            int run = SCAN ? tot[s] + before[i] : blk_base[(size_t)blockIdx.x * S + s];
+#pragma unroll
+            for (int w = 0; w < kPermWaves; ++w) {
+                cursor[w][s] = run;
+                run += wtot[w][s];
+            }
         }
     }
     __syncthreads();
@@ -288,10 +350,15 @@ int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const
     else {
         hipLaunchKernelGGL(slot_hist_kernel, dim3(nblk), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot,
                            blk_counts, P, s.top_k, s.V, s.E, s.S);
-        hipLaunchKernelGGL(slot_scan_kernel, dim3(1), dim3(kPermThreads), 0, st, blk_counts, blk_base, counts,
-                           offsets, nblk, s.S, tiles);
-        hipLaunchKernelGGL(slot_scatter_kernel, dim3(nblk), dim3(kPermThreads), 0, st, slot, blk_base, perm,
-                           inv_perm, P, s.S);
+        if ((int64_t)nblk * s.S <= kOwnScanMax) {
+            hipLaunchKernelGGL(slot_scatter_kernel<true>, dim3(nblk + 1), dim3(kPermThreads), 0, st, slot, blk_base,
+                               blk_counts, nblk, counts, offsets, perm, inv_perm, P, s.S, tiles);
+        } else {
+            hipLaunchKernelGGL(slot_scan_kernel, dim3(1), dim3(kPermThreads), 0, st, blk_counts, blk_base, counts,
+                               offsets, nblk, s.S, tiles);
+            hipLaunchKernelGGL(slot_scatter_kernel<false>, dim3(nblk), dim3(kPermThreads), 0, st, slot, blk_base,
+                               blk_counts, nblk, counts, offsets, perm, inv_perm, P, s.S, TileJob());
+        }
     }
     if (!Xg) return launch_status();
     const int row_vec = (int)((size_t)s.d_model * elem_size(s.dtype) / 16);
