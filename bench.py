@@ -32,12 +32,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).  The figures belong
 # to one version of the kernel source; with any other version `traffic` is null.
 TRAFFIC = {
-    "ffn_tiled.hip": {"sha256": "a266c2cbe0fe93b3fc6bb676b1e3152932c77ddf6da6ed56db0b979da5ee5ffd",
+    "ffn_tiled.hip": {"sha256": "d9e61b15169ed91120dae92792a8c9ab4fa0f5b72021b7b162908a1d54ec373f",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 11060124417, "write_bytes": 469762358},
-    "ffn_skinny.hip": {"sha256": "50b460970d089d7c122e7f3ef741fae8eb6cdc5db845ca63ed882d4a717e9ba2",
+                      "fetch_bytes": 11066329567, "write_bytes": 469762294},
+    "ffn_skinny.hip": {"sha256": "6251fdfca2475672fcf8c0de351e5d1c7ea8df1bf17f56ce71ef8f3fdd6a3716",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3067991223, "write_bytes": 3670613},
+                       "fetch_bytes": 3067877298, "write_bytes": 3670613},
 }
 
 
