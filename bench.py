@@ -30,14 +30,15 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch; summaries under profiles/), each scaled by
 # what the same counter reads for a plain 1 GiB device copy (--copy-calibration): FETCH_SIZE
 # reads 0.5 KiB per KiB copied (factor 2.0), WRITE_SIZE 1.0 (factor 1.0).  The figures belong
-# to one version of the kernel source; with any other version `traffic` is null.
+# to one version of the kernel's sources (the kernel file and the tile-list builder that decides
+# which tiles it runs); with any other version `traffic` is null.
 TRAFFIC = {
-    "ffn_tiled.hip": {"sha256": "d9e61b15169ed91120dae92792a8c9ab4fa0f5b72021b7b162908a1d54ec373f",
+    "ffn_tiled.hip": {"sources": ("ffn_tiled.hip", "tile_table.h"), "sha256": "2ee2a27d4e16500b7c0fbb1caf50f70a0b1e8d34f09380639baa2dbc603e3a72",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 11066329567, "write_bytes": 469762294},
-    "ffn_skinny.hip": {"sha256": "6251fdfca2475672fcf8c0de351e5d1c7ea8df1bf17f56ce71ef8f3fdd6a3716",
+                      "fetch_bytes": 11021548182, "write_bytes": 469762240},
+    "ffn_skinny.hip": {"sources": ("ffn_skinny.hip",), "sha256": "6251fdfca2475672fcf8c0de351e5d1c7ea8df1bf17f56ce71ef8f3fdd6a3716",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3067877298, "write_bytes": 3670613},
+                       "fetch_bytes": 3068066810, "write_bytes": 3670992},
 }
 
 
@@ -51,10 +52,11 @@ def measured_traffic(source, workload):
     import hashlib
 
     rec = TRAFFIC[source]
-    path = os.path.join(ROOT, "paper_2505_06481_amd", "csrc", source)
-    with open(path, "rb") as fh:
-        digest = hashlib.sha256(fh.read()).hexdigest()
-    if digest != rec["sha256"] or workload != rec["workload"]:
+    h = hashlib.sha256()
+    for name in rec["sources"]:
+        with open(os.path.join(ROOT, "paper_2505_06481_amd", "csrc", name), "rb") as fh:
+            h.update(fh.read())
+    if h.hexdigest() != rec["sha256"] or workload != rec["workload"]:
         return None
     return rec["fetch_bytes"] + rec["write_bytes"]
 
