@@ -291,6 +291,16 @@ def test_limits_many_slots_and_widest_router(mm, gc, oracle):
     cfg = synth.Config("many_slots_tiled", 6000, 256, 256, 8, 16, 2, "bf16", "swiglu", seed=23, share_prob=0.3)
     case, ref = staged_vs_oracle(mm, gc, oracle, cfg)
     assert case.S > 80
+    # several hundred slots and more pairs than one grouping workgroup takes: the scatter workgroups sum
+    # four slots per thread of the per-workgroup histograms themselves
+    cfg = synth.Config("many_slots_two_chunks", 1200, 256, 256, 64, 16, 2, "bf16", "swiglu", seed=30, share_prob=0.1)
+    case, ref = staged_vs_oracle(mm, gc, oracle, cfg)
+    assert 800 < case.S <= 1024
+    # the same pool with enough rows per slot for the matrix-core kernels: nine hundred short tile lists,
+    # a target height chosen over all of them
+    cfg = synth.Config("many_slots_tiled_wide", 20000, 256, 256, 64, 16, 2, "bf16", "relu", seed=31, share_prob=0.1)
+    case, ref = staged_vs_oracle(mm, gc, oracle, cfg)
+    assert 800 < case.S <= 1024 and mm.expert_plan(case.shape)[0] is False
 
 
 @pytest.mark.parametrize("name", ["switch8_fp32_v2_t128", "switch8_bf16_v4_t4096", "mixtral_decode_bf16_v2_t64"])
