@@ -314,7 +314,10 @@ def test_layer_forward_in_a_captured_graph(mm, gc, oracle):
     it into a HIP graph.  Every replay, with new tokens written into the same buffers in
     between and eager work around it, must reproduce the eager result bit for bit."""
     for cfg in (synth.Config("graph_stream", 48, 512, 768, 2, 4, 2, "bf16", "swiglu", seed=24),
-                synth.Config("graph_tiled", 800, 256, 512, 2, 4, 2, "bf16", "swiglu", seed=25)):
+                synth.Config("graph_tiled", 800, 256, 512, 2, 4, 2, "bf16", "swiglu", seed=25),
+                # one pick per token: three launches (stream) or five (tiled), the down product writes Y
+                synth.Config("graph_stream_top1", 40, 256, 512, 3, 8, 1, "f32", "gelu", seed=32, gate="all"),
+                synth.Config("graph_tiled_top1", 2500, 256, 512, 3, 8, 1, "bf16", "relu", seed=33, gate="all")):
         case = gc.DeviceCase(cfg)
         sh = case.shape
         Y = torch.empty((cfg.T, cfg.d_model), dtype=case.X.dtype, device="cuda")
@@ -342,7 +345,7 @@ def test_layer_forward_in_a_captured_graph(mm, gc, oracle):
             assert torch.equal(got, eager), f"{cfg.name}: replay {rep} differs from the eager result"
         # and against the oracle once, for the last batch (same pool and table, new tokens)
         last = dict(case.inp, X=inp["X"], vid=inp["vid"])
-        ref = oracle.layer_forward(last, cfg.top_k, cfg.dtype, cfg.act)
+        ref = oracle.layer_forward(last, cfg.top_k, cfg.dtype, cfg.act, gate=cfg.gate)
         gc.assert_close(gc.to_np64(got), ref["Y"], cfg.dtype, "Y (graph replay)")
 
 
