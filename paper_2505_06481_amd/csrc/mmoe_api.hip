@@ -228,7 +228,8 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
         if (!fold && (rc = launch_combine(*shape, Yg, nullptr, topk_w, Y, st))) return rc;
         return mark(MMOE_EV_COMBINE);
     }
-    if ((rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st))) return rc;
+    // the router also looks its picks up in the expert map (step M): the grouping starts from slot[]
+    if ((rc = launch_route(*shape, X, vid, Wr, br, topk_idx, topk_w, st, M, (int32_t*)(w + L.slot)))) return rc;
     if ((rc = mark(MMOE_EV_ROUTE))) return rc;
     // no gathered copy of the token rows: the up product reads X through perm
     int32_t* perm = (int32_t*)(w + L.perm);
@@ -236,7 +237,7 @@ int mmoe_layer_forward_events(const mmoe_shape* shape, const void* X, const int3
     int32_t* tile_tab = (int32_t*)(w + L.tile_tab);
     rc = launch_permute(*shape, X, vid, topk_idx, M, (int32_t*)(w + L.slot), (int32_t*)(w + L.counts), offsets,
                         perm, inv_perm, nullptr, (int32_t*)(w + L.blk_counts), (int32_t*)(w + L.blk_base), L.nblk,
-                        st, tiled ? tile_tab : nullptr);
+                        st, tiled ? tile_tab : nullptr, true);
     if (rc) return rc;
     if ((rc = mark(MMOE_EV_PERMUTE))) return rc;
     sink.perm = perm;

@@ -76,10 +76,12 @@ int launch_route(const mmoe_shape& s, const void* X, const int32_t* vid, const v
 // `Xg` null: everything but the row gather (the fused layer reads token rows through `perm`).
 // `tile_tab` given: the kernel that finishes the grouping also writes the tile lists of the
 // matrix-core expert kernels there (launch_ffn_tiled is then called with tab_ready).
+// `slot_ready`: the router has already written slot[] (launch_route with M and slot): the lookup is not
+// repeated where the grouping can do without its histogram kernel.
 int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const int32_t* topk_idx,
                    const int32_t* M, int32_t* slot, int32_t* counts, int32_t* offsets, int32_t* perm,
                    int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk,
-                   hipStream_t st, int32_t* tile_tab = nullptr);
+                   hipStream_t st, int32_t* tile_tab = nullptr, bool slot_ready = false);
 // Expert stage.  Row r of the grouped input is rows[r] when `perm` is null (rows = Xg), and
 // rows[perm[r] / top_k] otherwise (rows = X: the gather is folded into the up product's loads).
 // `mid`, when not null, is recorded between the up product (+ activation) and the down product.

@@ -20,6 +20,7 @@ constexpr int kPermThreads = 256;
 static_assert(kPermThreads == 256, "build_tile_lists is written for one workgroup of 256 threads");
 constexpr int kPermWaves = kPermThreads / kWave;
 constexpr int kPairsPerWave = kPermChunk / kPermWaves;  // 512
+constexpr int kOwnHistMaxBlk = 8;     // most grouping workgroups (of 2048 pairs) that each count the whole batch's slots themselves
 constexpr int kOwnScanMax = 1 << 14;  // most per-workgroup counts (workgroups x slots) a scatter workgroup sums by itself
 static_assert(kMaxS % kPermThreads == 0, "slots per thread");
 
@@ -123,13 +124,18 @@ __device__ __forceinline__ void place_pairs(volatile int* cur, int s, bool valid
     __builtin_amdgcn_wave_barrier();
 }
 
-// perm / inv_perm: stable ranks from ballots.
-// SCAN = false: the first output row of this workgroup's pairs of every slot comes from `blk_base`
-// (written by slot_scan_kernel).  SCAN = true (few workgroups, few slots: the table of per-workgroup
-// counts is small): every workgroup sums that table itself, so the scan kernel and its launch are not
-// needed; the grid has one more workgroup, which places no pairs and writes counts, offsets and the
-// tile lists instead.
-template <bool SCAN>
+// perm / inv_perm: stable ranks from ballots.  Where the first output row of this workgroup's pairs of
+// every slot comes from:
+//   kFromScan    `blk_base`, written by slot_scan_kernel;
+//   kOwnScan     few workgroups, few slots, so the table of per-workgroup counts is small: every
+//                workgroup sums that table itself, and the scan kernel and its launch are not needed;
+//   kOwnHist     few workgroups, and slot[] already written by the router: every workgroup counts the
+//                pairs in front of its own and the pairs of the whole batch itself (a read of P integers
+//                and integer LDS atomics), and the histogram kernel is not needed either.
+// In the last two the grid has one more workgroup, which places no pairs and writes counts, offsets and
+// the tile lists instead.
+enum { kFromScan = 0, kOwnScan = 1, kOwnHist = 2 };
+template <int SRC>
 __global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_t* __restrict__ slot,
                                                                     const int32_t* __restrict__ blk_base,
                                                                     const int32_t* __restrict__ blk_counts, int nblk,
@@ -141,24 +147,46 @@ __global__ __launch_bounds__(kPermThreads) void slot_scatter_kernel(const int32_
 {
     __shared__ int wtot[kPermWaves][kMaxS];  // pairs of each slot owned by each wavefront
     __shared__ int cursor[kPermWaves][kMaxS];
+    constexpr bool SCAN = SRC != kFromScan;
     __shared__ int tot[SCAN ? kMaxS : 1];      // pairs of each slot in the whole batch, then its first row
+    __shared__ int lower[SRC == kOwnHist ? kMaxS : 1];  // pairs of each slot in front of this workgroup's
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int sbits = 32 - __clz(max(S - 1, 1));  // bits of a slot id
     int before[kMaxS / kPermThreads];             // this workgroup's first row of slot threadIdx.x + 256 i
     if (SCAN) {
         const int b = blockIdx.x;  // nblk: the workgroup that writes the tables
+        if (SRC == kOwnHist) {
+            for (int sl = threadIdx.x; sl < S; sl += kPermThreads) {
+                tot[sl] = 0;
+                lower[sl] = 0;
+            }
+            __syncthreads();
+            const int first = b * kPermChunk;  // this workgroup's first pair (the table writer's: unused)
+            for (int p = threadIdx.x; p < P; p += kPermThreads) {
+                const int sl = slot[p];
+                atomicAdd(&tot[sl], 1);  // integer LDS atomics: the sums do not depend on order
+                if (p < first) atomicAdd(&lower[sl], 1);
+            }
+            __syncthreads();
 #pragma unroll
-        for (int i = 0; i < kMaxS / kPermThreads; ++i) {
-            const int sl = threadIdx.x + i * kPermThreads;
-            int run = 0, mine = 0;
-            if (sl < S)
-                for (int bb = 0; bb < nblk; ++bb) {
-                    if (bb == b) mine = run;
-                    run += blk_counts[(size_t)bb * S + sl];
-                }
-            before[i] = mine;
-            if (sl < S) tot[sl] = run;
+            for (int i = 0; i < kMaxS / kPermThreads; ++i) {
+                const int sl = threadIdx.x + i * kPermThreads;
+                before[i] = sl < S ? lower[sl] : 0;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kMaxS / kPermThreads; ++i) {
+                const int sl = threadIdx.x + i * kPermThreads;
+                int run = 0, mine = 0;
+                if (sl < S)
+                    for (int bb = 0; bb < nblk; ++bb) {
+                        if (bb == b) mine = run;
+                        run += blk_counts[(size_t)bb * S + sl];
+                    }
+                before[i] = mine;
+                if (sl < S) tot[sl] = run;
+            }
         }
         __syncthreads();
         if (b == nblk)
@@ -340,23 +368,26 @@ int launch_validate(const mmoe_shape& s, const int32_t* vid, const int32_t* M, i
 int launch_permute(const mmoe_shape& s, const void* X, const int32_t* vid, const int32_t* topk_idx,
                    const int32_t* M, int32_t* slot, int32_t* counts, int32_t* offsets, int32_t* perm,
                    int32_t* inv_perm, void* Xg, int32_t* blk_counts, int32_t* blk_base, int nblk, hipStream_t st,
-                   int32_t* tile_tab)
+                   int32_t* tile_tab, bool slot_ready)
 {
     const int P = s.T * s.top_k;
     const TileJob tiles = tile_job(s, tile_tab);
     if (nblk == 1)
         hipLaunchKernelGGL(slot_group_small_kernel, dim3(1), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot, counts,
                            offsets, perm, inv_perm, P, s.top_k, s.V, s.E, s.S, tiles);
-    else {
+    else if (slot_ready && nblk <= kOwnHistMaxBlk) {
+        hipLaunchKernelGGL(slot_scatter_kernel<kOwnHist>, dim3(nblk + 1), dim3(kPermThreads), 0, st, slot, blk_base,
+                           blk_counts, nblk, counts, offsets, perm, inv_perm, P, s.S, tiles);
+    } else {
         hipLaunchKernelGGL(slot_hist_kernel, dim3(nblk), dim3(kPermThreads), 0, st, vid, topk_idx, M, slot,
                            blk_counts, P, s.top_k, s.V, s.E, s.S);
         if ((int64_t)nblk * s.S <= kOwnScanMax) {
-            hipLaunchKernelGGL(slot_scatter_kernel<true>, dim3(nblk + 1), dim3(kPermThreads), 0, st, slot, blk_base,
+            hipLaunchKernelGGL(slot_scatter_kernel<kOwnScan>, dim3(nblk + 1), dim3(kPermThreads), 0, st, slot, blk_base,
                                blk_counts, nblk, counts, offsets, perm, inv_perm, P, s.S, tiles);
         } else {
             hipLaunchKernelGGL(slot_scan_kernel, dim3(1), dim3(kPermThreads), 0, st, blk_counts, blk_base, counts,
                                offsets, nblk, s.S, tiles);
-            hipLaunchKernelGGL(slot_scatter_kernel<false>, dim3(nblk), dim3(kPermThreads), 0, st, slot, blk_base,
+            hipLaunchKernelGGL(slot_scatter_kernel<kFromScan>, dim3(nblk), dim3(kPermThreads), 0, st, slot, blk_base,
                                blk_counts, nblk, counts, offsets, perm, inv_perm, P, s.S, TileJob());
         }
     }

@@ -146,12 +146,23 @@ __device__ __forceinline__ void build_tile_lists(const int32_t* offsets, int32_t
         __syncthreads();  // the lists of the product before have been written: base and part are free
         part[tid] = mine;
         __syncthreads();
-        for (int dlt = 1; dlt < 256; dlt <<= 1) {
-            const int add = tid >= dlt ? part[tid - dlt] : 0;
-            __syncthreads();
-            part[tid] += add;
-            __syncthreads();
+        if (tid < kWave) {  // inclusive scan of the 256 runs by the first wavefront: four per lane, then across the lanes
+            int v[4], sum = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                sum += part[4 * tid + i];
+                v[i] = sum;
+            }
+            int incl = sum;
+#pragma unroll
+            for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+                const int o = __shfl_up(incl, dlt, kWave);
+                if (tid >= dlt) incl += o;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) part[4 * tid + i] = incl - sum + v[i];
         }
+        __syncthreads();
         int run = part[tid] - mine;
         for (int s = s_lo; s < s_hi; ++s) {
             base[s] = run;
