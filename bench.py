@@ -33,12 +33,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # to one version of the kernel's sources (the kernel file and the tile-list builder that decides
 # which tiles it runs); with any other version `traffic` is null.
 TRAFFIC = {
-    "ffn_tiled.hip": {"sources": ("ffn_tiled.hip", "tile_table.h"), "sha256": "2ee2a27d4e16500b7c0fbb1caf50f70a0b1e8d34f09380639baa2dbc603e3a72",
+    "ffn_tiled.hip": {"sources": ("ffn_tiled.hip", "tile_table.h"), "sha256": "010729f1edd0a95d7f56e6be3a7c729c20803eaf7298375dcf71424eaabbcee0",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 11021548182, "write_bytes": 469762240},
+                      "fetch_bytes": 10970896852, "write_bytes": 469762348},
     "ffn_skinny.hip": {"sources": ("ffn_skinny.hip",), "sha256": "6251fdfca2475672fcf8c0de351e5d1c7ea8df1bf17f56ce71ef8f3fdd6a3716",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3068066810, "write_bytes": 3670992},
+                       "fetch_bytes": 3067992111, "write_bytes": 3670757},
 }
 
 
