@@ -35,10 +35,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 TRAFFIC = {
     "ffn_tiled.hip": {"sources": ("ffn_tiled.hip", "tile_table.h"), "sha256": "010729f1edd0a95d7f56e6be3a7c729c20803eaf7298375dcf71424eaabbcee0",
                       "workload": "mixtral_prefill_bf16_v2_t8192",
-                      "fetch_bytes": 10970896852, "write_bytes": 469762348},
+                      "fetch_bytes": 10971821914, "write_bytes": 469762380},
     "ffn_skinny.hip": {"sources": ("ffn_skinny.hip",), "sha256": "6251fdfca2475672fcf8c0de351e5d1c7ea8df1bf17f56ce71ef8f3fdd6a3716",
                        "workload": "mixtral_decode_bf16_v2_t64",
-                       "fetch_bytes": 3067992111, "write_bytes": 3670757},
+                       "fetch_bytes": 3068027183, "write_bytes": 3670794},
 }
 
 
